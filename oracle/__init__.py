@@ -1,0 +1,12 @@
+"""CPU checker for the densify path.  TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import
+this package; the GPU library and its Python binding never do.
+"""
+from .reference import (  # noqa: F401
+    OracleResult,
+    buffer_bytes,
+    densify,
+    densify_timed,
+    unique_ids,
+)
