@@ -1,0 +1,146 @@
+/*
+ * ts_densify -- densify an assumed-sparse gradient on one MI355X (gfx950).
+ *
+ * The operation (arXiv 1905.04035): a transformer whose embedding matrix is shared
+ * with the pre-softmax projection receives, for that one [V, d] weight, sparse
+ * gradients from the encoder and decoder embedding lookups (one (id, row) slice
+ * per looked-up token, ids repeat) and one dense [V, d] gradient from the
+ * projection (Section 3).  Section 4, Listing 1 converts each sparse gradient to a
+ * dense tensor so that a fixed-size reduce replaces an ever-growing gather;
+ * Section 6, Algorithm 2 (the added branch) converts every gradient to dense and
+ * sums them.  These entry points compute exactly that sum:
+ *
+ *     dense_out[v, :] = dense_in[v, :] + sum over pairs t with ids[t] == v of rows[t, :]
+ *
+ * Conventions common to all calls
+ *   - Pointers named ids, rows, dense_in, dense_out and the workspace are DEVICE
+ *     pointers owned by the caller.  The library never frees them and does not
+ *     keep them after the work it enqueued on `stream` has run.  Arrays named *_k
+ *     and every out-parameter of a query are HOST pointers.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work
+ *     is enqueued; no call synchronises the host or allocates device memory.
+ *   - Layout: ids int32 [n]; rows [n, d] row-major, fp32 or bf16 bit patterns;
+ *     dense_in / dense_out fp32 [V, d] row-major.  rows, dense_in and dense_out
+ *     must be 16-byte aligned and d must be a multiple of 4.
+ *   - dense_in == NULL means "no dense operand" (Listing 1 alone): rows that
+ *     receive no pair are +0.0.  dense_out == dense_in (the same pointer) is
+ *     allowed and updates in place; any other overlap is undefined.
+ *   - Rows that receive no pair are copied from dense_in bit for bit.
+ *   - A pair whose id is outside [0, V) is skipped, never dereferenced, and
+ *     counted; the count is visible through ts_last_views (n_bad_ids).
+ *   - Sums are fp32.  Within one output row the pairs are added in input order
+ *     inside fixed-size pieces, the pieces are combined in a fixed order and
+ *     dense_in is added last; no floating-point atomics are used, so the same
+ *     inputs give the same bits on every run.
+ *   - Return value: TS_OK or a ts_status; it covers only what the host can check
+ *     (arguments, workspace, launch errors).
+ *   - One call at a time per process: calls share the bound workspace.
+ */
+#ifndef TS_DENSIFY_H
+#define TS_DENSIFY_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TS_OK = 0,
+    TS_ERR_NULL = 1,      /* a required pointer is NULL */
+    TS_ERR_SHAPE = 2,     /* n < 0, V <= 0, d <= 0, d % 4 != 0, k out of range, unknown dtype */
+    TS_ERR_ALIGN = 3,     /* rows / dense_in / dense_out not 16-byte aligned */
+    TS_ERR_WORKSPACE = 4, /* no workspace bound, or it is too small for this call */
+    TS_ERR_HIP = 5,       /* the HIP runtime reported an error (launch, event) */
+    TS_ERR_OVERFLOW = 6   /* a size does not fit (n_total >= 2^31, byte count overflow) */
+} ts_status;
+
+enum { TS_ROW_FP32 = 0, TS_ROW_BF16 = 1 };
+
+/* Largest k accepted by ts_densify_multi (shard descriptors travel as kernel arguments). */
+#define TS_MAX_SHARDS 64
+
+/*
+ * Densify one sparse gradient with fp32 value rows and add the dense one
+ * (Section 4, Listing 1; Section 6, Algorithm 2, added branch).
+ * n may be 0 (then dense_out = dense_in, or zeros).
+ */
+int ts_densify(const int32_t* ids, const float* rows, int64_t n, int32_t d, int32_t V,
+               const float* dense_in, float* dense_out, void* stream);
+
+/* Same, value rows stored as bf16 bit patterns; they are widened exactly and summed in fp32. */
+int ts_densify_bf16(const int32_t* ids, const uint16_t* rows, int64_t n, int32_t d, int32_t V,
+                    const float* dense_in, float* dense_out, void* stream);
+
+/*
+ * Densify k contributions at once: the result is that of ts_densify on their
+ * concatenation in shard order (Section 3: under the gather strategy the
+ * accumulate buffer is the concatenation of every worker's slices).
+ * ids_k[j], rows_k[j] (device pointers) and n_k[j] describe shard j; the three
+ * arrays themselves are host arrays of length k, read before the call returns.
+ * 1 <= k <= TS_MAX_SHARDS; shards may be empty and of different lengths; a
+ * contiguous gathered buffer is the case k = 1.  row_dtype is TS_ROW_FP32 or
+ * TS_ROW_BF16 for all shards.
+ */
+int ts_densify_multi(const int32_t* const* ids_k, const void* const* rows_k, const int64_t* n_k,
+                     int32_t k, int32_t row_dtype, int32_t d, int32_t V,
+                     const float* dense_in, float* dense_out, void* stream);
+
+/*
+ * Bytes of the two accumulate buffers the paper compares (Section 4, Fig. 5a):
+ * gathered = k * N * (4 + elem * d) for k workers of N slices each (int32 id plus
+ * d values of elem bytes), dense = 4 * V * d whatever k is.  Pure host arithmetic.
+ */
+int ts_buffer_bytes(int64_t k, int64_t N, int32_t d, int32_t V, int32_t row_dtype,
+                    int64_t* gathered_bytes, int64_t* dense_bytes);
+
+/*
+ * Workspace.  The caller allocates device memory (256-byte aligned) of at least
+ * ts_workspace_bytes(n_total, d, V) and binds it once; every later call with
+ * n <= n_total and d, V no larger reuses it.  Its contents need no initialisation.
+ * The library holds the pointer until another workspace is bound (ws == NULL
+ * unbinds); a call that needs more than the bound bytes returns TS_ERR_WORKSPACE.
+ */
+int ts_workspace_bytes(int64_t n_total, int32_t d, int32_t V, int64_t* bytes);
+int ts_bind_workspace(void* ws, int64_t bytes);
+
+/*
+ * Views into the bound workspace describing the most recent densify call, valid
+ * (in stream order) until the next one: count int32 [V] pairs per row,
+ * row_start int32 [V + 1] exclusive prefix of count, perm int32 [n_valid] input
+ * positions sorted by (id, position), n_valid and n_bad_ids int32 scalars.  Any
+ * out-pointer may be NULL.  All returned pointers are device pointers.
+ */
+int ts_last_views(const int32_t** count, const int32_t** row_start, const int32_t** perm,
+                  const int32_t** n_valid, const int32_t** n_bad_ids);
+
+/*
+ * Ascending list of the rows that received at least one pair in the most recent
+ * call: writes unique_ids_out[0 .. n_unique) (device, capacity >= min(n, V)
+ * int32) and *n_unique_out (device int32).  Enqueues one small kernel.
+ */
+int ts_unique_ids(int32_t* unique_ids_out, int32_t* n_unique_out, void* stream);
+
+/*
+ * Per-kernel timing for benchmarks.  ts_profile_begin(capacity) makes each of the
+ * next `capacity` densify calls record a HIP event pair around its row-reduce
+ * kernel on the caller's stream; ts_profile_end waits for those events and writes
+ * up to `capacity` durations in milliseconds to ms_out (host) and how many to
+ * *n_out (host), then stops recording.  capacity <= 4096.
+ */
+int ts_profile_begin(int32_t capacity);
+int ts_profile_end(float* ms_out, int32_t capacity, int32_t* n_out);
+
+/*
+ * Tuning.  piece_tokens: sorted positions handled by one wavefront item of the
+ * row-reduce kernel (8, 16 or 32; 0 = choose from n).  Changes the fixed
+ * summation order (still deterministic) and the workspace size.
+ */
+int ts_set_piece_tokens(int32_t piece_tokens);
+
+const char* ts_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TS_DENSIFY_H */

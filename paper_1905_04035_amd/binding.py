@@ -1,0 +1,222 @@
+"""ctypes binding of libts_densify.so: the same names as include/ts_densify.h.
+
+Argument marshalling only.  Tensors are PyTorch tensors on the GPU (PyTorch is
+used for device memory and streams, nothing else); every step of the path runs
+in the library's kernels.  There is no fallback: if the library is missing or a
+call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import torch
+
+TS_OK = 0
+TS_ERR_NULL, TS_ERR_SHAPE, TS_ERR_ALIGN, TS_ERR_WORKSPACE, TS_ERR_HIP, TS_ERR_OVERFLOW = 1, 2, 3, 4, 5, 6
+TS_ROW_FP32, TS_ROW_BF16 = 0, 1
+TS_MAX_SHARDS = 64
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libts_densify.so")
+
+_lib = None
+
+
+class TsError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+def lib():
+    """The loaded library.  Raises if it has not been built (run build.py)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_1905_04035_amd.build`")
+        l = C.CDLL(LIB_PATH)
+        vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+        l.ts_densify.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
+        l.ts_densify_bf16.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
+        l.ts_densify_multi.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, vp]
+        l.ts_buffer_bytes.argtypes = [i64, i64, i32, i32, i32, vp, vp]
+        l.ts_workspace_bytes.argtypes = [i64, i32, i32, vp]
+        l.ts_bind_workspace.argtypes = [vp, i64]
+        l.ts_last_views.argtypes = [vp, vp, vp, vp, vp]
+        l.ts_unique_ids.argtypes = [vp, vp, vp]
+        l.ts_profile_begin.argtypes = [i32]
+        l.ts_profile_end.argtypes = [vp, i32, vp]
+        l.ts_set_piece_tokens.argtypes = [i32]
+        l.ts_status_string.argtypes = [C.c_int]
+        l.ts_status_string.restype = C.c_char_p
+        for name in ("ts_densify", "ts_densify_bf16", "ts_densify_multi", "ts_buffer_bytes",
+                     "ts_workspace_bytes", "ts_bind_workspace", "ts_last_views", "ts_unique_ids",
+                     "ts_profile_begin", "ts_profile_end", "ts_set_piece_tokens"):
+            getattr(l, name).restype = C.c_int
+        _lib = l
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().ts_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != TS_OK:
+        raise TsError(status, where)
+
+
+def _p(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> C.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _check_dense(d: int, V: int, dense_in, dense_out):
+    assert dense_out.is_cuda and dense_out.dtype == torch.float32 and dense_out.is_contiguous()
+    assert tuple(dense_out.shape) == (V, d)
+    if dense_in is not None:
+        assert dense_in.is_cuda and dense_in.dtype == torch.float32 and dense_in.is_contiguous()
+        assert tuple(dense_in.shape) == (V, d)
+
+
+def _check_pair(ids, rows, d: int, dtype):
+    assert ids.is_cuda and ids.dtype == torch.int32 and ids.is_contiguous()
+    assert rows.is_cuda and rows.dtype == dtype and rows.is_contiguous()
+    assert rows.numel() == ids.numel() * d
+
+
+# ---- raw calls (return the status; used by the error-path tests) -------------------------------
+def ts_densify_raw(ids_ptr, rows_ptr, n, d, V, dense_in_ptr, dense_out_ptr, stream_ptr=None) -> int:
+    return lib().ts_densify(ids_ptr, rows_ptr, n, d, V, dense_in_ptr, dense_out_ptr, stream_ptr)
+
+
+# ---- the entry points ----------------------------------------------------------------------------
+def ts_densify(ids: torch.Tensor, rows: torch.Tensor, d: int, V: int,
+               dense_in: Optional[torch.Tensor], dense_out: torch.Tensor, stream=None) -> None:
+    _check_pair(ids, rows, d, torch.float32)
+    _check_dense(d, V, dense_in, dense_out)
+    _check(lib().ts_densify(_p(ids), _p(rows), ids.numel(), d, V, _p(dense_in), _p(dense_out),
+                            _stream(stream)), "ts_densify")
+
+
+def ts_densify_bf16(ids: torch.Tensor, rows: torch.Tensor, d: int, V: int,
+                    dense_in: Optional[torch.Tensor], dense_out: torch.Tensor, stream=None) -> None:
+    """rows: uint16 / int16 / bfloat16 tensor holding bf16 bit patterns."""
+    assert rows.element_size() == 2
+    _check_pair(ids, rows, d, rows.dtype)
+    _check_dense(d, V, dense_in, dense_out)
+    _check(lib().ts_densify_bf16(_p(ids), _p(rows), ids.numel(), d, V, _p(dense_in), _p(dense_out),
+                                 _stream(stream)), "ts_densify_bf16")
+
+
+def ts_densify_multi(ids_k: Sequence[torch.Tensor], rows_k: Sequence[torch.Tensor], row_dtype: int,
+                     d: int, V: int, dense_in: Optional[torch.Tensor], dense_out: torch.Tensor,
+                     stream=None) -> None:
+    k = len(ids_k)
+    assert k == len(rows_k)
+    for i, r in zip(ids_k, rows_k):
+        assert r.element_size() == (2 if row_dtype == TS_ROW_BF16 else 4)
+        _check_pair(i, r, d, r.dtype)
+    _check_dense(d, V, dense_in, dense_out)
+    ids_arr = (C.c_void_p * max(k, 1))(*[i.data_ptr() for i in ids_k])
+    rows_arr = (C.c_void_p * max(k, 1))(*[r.data_ptr() for r in rows_k])
+    n_arr = (C.c_int64 * max(k, 1))(*[i.numel() for i in ids_k])
+    _check(lib().ts_densify_multi(ids_arr, rows_arr, n_arr, k, row_dtype, d, V, _p(dense_in),
+                                  _p(dense_out), _stream(stream)), "ts_densify_multi")
+
+
+def ts_buffer_bytes(k: int, N: int, d: int, V: int, row_dtype: int = TS_ROW_FP32):
+    g, dn = C.c_int64(0), C.c_int64(0)
+    _check(lib().ts_buffer_bytes(k, N, d, V, row_dtype, C.byref(g), C.byref(dn)), "ts_buffer_bytes")
+    return g.value, dn.value
+
+
+def ts_workspace_bytes(n_total: int, d: int, V: int) -> int:
+    b = C.c_int64(0)
+    _check(lib().ts_workspace_bytes(n_total, d, V, C.byref(b)), "ts_workspace_bytes")
+    return b.value
+
+
+def ts_bind_workspace(ws: Optional[torch.Tensor]) -> None:
+    if ws is None:
+        _check(lib().ts_bind_workspace(None, 0), "ts_bind_workspace")
+        return
+    assert ws.is_cuda and ws.is_contiguous()
+    _check(lib().ts_bind_workspace(_p(ws), ws.numel() * ws.element_size()), "ts_bind_workspace")
+
+
+class Workspace:
+    """Device scratch for calls of up to n_total pairs; keeps the tensor alive while bound."""
+
+    def __init__(self, n_total: int, d: int, V: int, device="cuda:0"):
+        self.bytes = ts_workspace_bytes(n_total, d, V)
+        self.tensor = torch.empty(self.bytes, dtype=torch.uint8, device=device)
+        ts_bind_workspace(self.tensor)
+
+    def close(self):
+        ts_bind_workspace(None)
+        self.tensor = None
+
+
+def ts_last_views(V: int, n: int):
+    """(count[V], row_start[V+1], perm[n_valid], n_valid, n_bad_ids) of the last call, copied to
+    the host after a synchronise."""
+    ptrs = [C.c_void_p() for _ in range(5)]
+    _check(lib().ts_last_views(*[C.byref(p) for p in ptrs]), "ts_last_views")
+    torch.cuda.synchronize()
+
+    def fetch(ptr, count):
+        if count == 0:
+            return torch.empty(0, dtype=torch.int32)
+        host = torch.empty(count, dtype=torch.int32)
+        rc = _hip().hipMemcpy(C.c_void_p(host.data_ptr()), ptr, C.c_size_t(4 * count), C.c_int(2))
+        if rc != 0:
+            raise RuntimeError(f"hipMemcpy failed with {rc}")
+        return host
+
+    n_valid = int(fetch(ptrs[3], 1)[0])
+    n_bad = int(fetch(ptrs[4], 1)[0])
+    return fetch(ptrs[0], V), fetch(ptrs[1], V + 1), fetch(ptrs[2], min(n_valid, n)), n_valid, n_bad
+
+
+_hiprt = None
+
+
+def _hip():
+    global _hiprt
+    if _hiprt is None:
+        _hiprt = C.CDLL("libamdhip64.so")
+        _hiprt.hipMemcpy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int]
+        _hiprt.hipMemcpy.restype = C.c_int
+    return _hiprt
+
+
+def ts_unique_ids(capacity: int, stream=None, device="cuda:0"):
+    """Ascending ids that received at least one pair in the last call (host tensor)."""
+    out = torch.empty(max(capacity, 1), dtype=torch.int32, device=device)
+    n_out = torch.zeros(1, dtype=torch.int32, device=device)
+    _check(lib().ts_unique_ids(_p(out), _p(n_out), _stream(stream)), "ts_unique_ids")
+    m = int(n_out.cpu()[0])
+    return out[:m].cpu()
+
+
+def ts_profile_begin(capacity: int) -> None:
+    _check(lib().ts_profile_begin(capacity), "ts_profile_begin")
+
+
+def ts_profile_end(capacity: int):
+    buf = (C.c_float * max(capacity, 1))()
+    n = C.c_int32(0)
+    _check(lib().ts_profile_end(buf, capacity, C.byref(n)), "ts_profile_end")
+    return [buf[i] for i in range(n.value)]
+
+
+def ts_set_piece_tokens(piece_tokens: int) -> None:
+    _check(lib().ts_set_piece_tokens(piece_tokens), "ts_set_piece_tokens")

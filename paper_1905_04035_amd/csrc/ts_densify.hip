@@ -1,0 +1,858 @@
+// ts_densify: densify an assumed-sparse gradient and add the dense one, on gfx950.
+//
+// The result is the one defined by arXiv 1905.04035, Section 4 (Listing 1: an
+// IndexedSlices gradient becomes a dense tensor) and Section 6 (Algorithm 2, added
+// branch: every gradient becomes dense, then they are summed):
+//
+//     dense_out[v,:] = dense_in[v,:] + sum_{t : ids[t] == v} rows[t,:]
+//
+// Three kernels per call, all on the caller's stream, no host synchronisation:
+//
+//   sort_kernel     stable counting sort of the pairs by id.  Work-group (g, s) owns
+//                   1024 consecutive ids and slice s of the pairs; its 16 wavefronts
+//                   count their sub-slices into LDS-private tables, an exclusive scan
+//                   turns the counts into offsets, and a second walk over the same
+//                   sub-slices hands every owned pair its final position.  A part's
+//                   first position is the number of pairs with a smaller id, which the
+//                   work-group counts itself while it scans, so parts never wait for
+//                   one another.  With one slice this is a single launch; with more,
+//                   a counting launch fills a [slice][id] table first.
+//   reduce_kernel   the HBM-bound kernel.  Wavefront items come in two kinds, heavy
+//                   first: (piece of C sorted positions, block of 256 columns), which
+//                   adds the value rows of every output row that starts in the piece
+//                   and writes dense_in + sum straight to dense_out; then (one
+//                   untouched output row), a 16-byte-per-lane streaming copy.  An
+//                   output row with more than C pairs is cut at piece boundaries; its
+//                   pieces go to scratch as fp32 partial rows.
+//   combine_kernel  for every cut row: partials added in piece order by 16 wavefronts
+//                   (contiguous shares, then the shares in order), dense_in added
+//                   last, result written to dense_out.
+//
+// No floating-point atomics anywhere: the position of every pair, the cut points and
+// the order of every addition depend on the ids alone, so results are reproducible
+// bit for bit.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string.h>
+
+#include "ts_densify.h"
+
+namespace {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+
+constexpr int kPart = 1024;        // ids owned by one sort work-group
+constexpr int kSortWaves = 16;     // wavefronts per sort work-group
+constexpr int kColBlock = 256;     // fp32 columns per wavefront item (64 lanes x 4)
+constexpr int kMaxSlices = 64;
+constexpr int kSliceTokens = 16384;
+constexpr int kFusedSortMax = 32768;   // up to here one launch sorts everything
+
+// ------------------------------------------------------------------ device helpers
+__device__ __forceinline__ uint64_t ballot64(bool p) { return __ballot(p); }
+
+__device__ __forceinline__ uint32_t lanes_below(uint64_t m)
+{
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+}
+
+__device__ __forceinline__ uint32_t bcast(uint32_t x, int lane) { return __builtin_amdgcn_readlane(x, lane); }
+
+__device__ __forceinline__ uint64_t bcast64(uint64_t x, int lane)
+{
+    uint32_t lo = __builtin_amdgcn_readlane((uint32_t)x, lane);
+    uint32_t hi = __builtin_amdgcn_readlane((uint32_t)(x >> 32), lane);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+__device__ __forceinline__ uint32_t wave_sum(uint32_t x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+    return x;
+}
+
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x, int lane)
+{
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        uint32_t y = __shfl_up(x, o, 64);
+        if (lane >= o) x += y;
+    }
+    return x;
+}
+
+// Value rows: four consecutive columns per lane, widened to fp32.
+template <typename RowT>
+__device__ __forceinline__ f4 load_row4(uint64_t row_addr, int col);
+
+template <>
+__device__ __forceinline__ f4 load_row4<float>(uint64_t row_addr, int col)
+{
+    return *reinterpret_cast<const f4*>(row_addr + (uint64_t)col * 4u);
+}
+
+template <>
+__device__ __forceinline__ f4 load_row4<uint16_t>(uint64_t row_addr, int col)
+{
+    u2 b = *reinterpret_cast<const u2*>(row_addr + (uint64_t)col * 2u);
+    f4 r;
+    r.x = __uint_as_float(b.x << 16);
+    r.y = __uint_as_float(b.x & 0xFFFF0000u);
+    r.z = __uint_as_float(b.y << 16);
+    r.w = __uint_as_float(b.y & 0xFFFF0000u);
+    return r;
+}
+
+__device__ __forceinline__ f4 load_f4(const float* p) { return *reinterpret_cast<const f4*>(p); }
+__device__ __forceinline__ void store_f4(float* p, f4 v) { *reinterpret_cast<f4*>(p) = v; }
+
+// ------------------------------------------------------------------ shard table
+struct ShardTable {
+    int32_t k;
+    int32_t off[TS_MAX_SHARDS + 1];          // first global pair index of each shard
+    const int32_t* ids[TS_MAX_SHARDS];
+    const char* rows[TS_MAX_SHARDS];
+};
+
+// Calls f(shard, global index, valid, id) for 64 pairs at a time over [a, b), in
+// increasing index order, never mixing two shards in one call.  a and b are
+// wave-uniform.
+template <typename F>
+__device__ __forceinline__ void for_each_tile(const ShardTable& sh, int a, int b, int lane, F&& f)
+{
+    if (a >= b) return;
+    int j = 0;
+    while (j < sh.k && sh.off[j + 1] <= a) ++j;
+    int t = a;
+    while (t < b && j < sh.k) {
+        const int hi = min(b, sh.off[j + 1]);
+        const int32_t* ids = sh.ids[j];
+        const int base = sh.off[j];
+        for (int tt = t; tt < hi; tt += 64) {
+            const int idx = tt + lane;
+            const bool valid = idx < hi;
+            const int32_t id = valid ? ids[idx - base] : -1;
+            f(j, idx, valid, id);
+        }
+        t = max(t, hi);
+        ++j;
+    }
+}
+
+// ------------------------------------------------------------------ sort
+struct SortParams {
+    int32_t n, V, G, S, SL;
+    int32_t row_bytes;
+    int32_t* count;
+    int32_t* row_start;
+    int32_t* perm;
+    int32_t* srt_id;
+    uint64_t* srt_addr;
+    uint32_t* tot;      // [S][G * kPart]  pairs per (slice, id)
+    uint32_t* below;    // [S][G]          pairs of the slice with a valid id below the part
+    uint32_t* bad;      // [S]             pairs of the slice with an id outside [0, V)
+    int32_t* n_valid;
+    int32_t* n_bad;
+};
+
+enum { SORT_FUSED = 0, SORT_COUNT = 1, SORT_SCATTER = 2 };
+
+template <int MODE>
+__global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
+{
+    __shared__ uint32_t cnt[kSortWaves][kPart];
+    __shared__ uint32_t red[3 * kSortWaves];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = blockIdx.x;
+    const int sl = blockIdx.y;
+    const int lo = g * kPart;
+    const uint32_t span = (uint32_t)min(kPart, p.V - lo);
+
+    for (int i = tid; i < kSortWaves * kPart; i += 1024) (&cnt[0][0])[i] = 0u;
+
+    const int t0 = sl * p.SL;
+    const int t1 = (int)min((int64_t)p.n, (int64_t)t0 + p.SL);
+    const int L = p.SL / kSortWaves;
+    const int a = (int)min((int64_t)t1, (int64_t)t0 + (int64_t)w * L);
+    const int b = (int)min((int64_t)t1, (int64_t)a + L);
+    __syncthreads();
+
+    // pass 1: count owned pairs per (wavefront, id); count what lies below the part
+    uint32_t below = 0, bad = 0;
+    for_each_tile(sh, a, b, lane, [&](int, int, bool valid, int32_t id) {
+        const uint32_t rel = (uint32_t)(id - lo);
+        if (valid && rel < span) atomicAdd(&cnt[w][rel], 1u);
+        below += (valid && id >= 0 && id < lo) ? 1u : 0u;
+        bad += (valid && (id < 0 || id >= p.V)) ? 1u : 0u;
+    });
+    __syncthreads();
+
+    uint32_t mine = 0;
+#pragma unroll
+    for (int ww = 0; ww < kSortWaves; ++ww) mine += cnt[ww][tid];
+    below = wave_sum(below);
+    bad = wave_sum(bad);
+    if (lane == 0) {
+        red[w] = below;
+        red[kSortWaves + w] = bad;
+    }
+    __syncthreads();
+    uint32_t below_wg = 0, bad_wg = 0;
+#pragma unroll
+    for (int ww = 0; ww < kSortWaves; ++ww) {
+        below_wg += red[ww];
+        bad_wg += red[kSortWaves + ww];
+    }
+
+    const size_t GV = (size_t)p.G * kPart;
+    if (MODE == SORT_COUNT) {
+        p.tot[(size_t)sl * GV + lo + tid] = mine;
+        if (tid == 0) {
+            p.below[sl * p.G + g] = below_wg;
+            if (g == 0) p.bad[sl] = bad_wg;
+        }
+        return;
+    }
+
+    uint32_t total = mine, pre = 0, base = below_wg, nbad = bad_wg;
+    if (MODE == SORT_SCATTER) {
+        total = 0;
+        base = 0;
+        nbad = 0;
+        for (int s2 = 0; s2 < p.S; ++s2) {
+            const uint32_t x = p.tot[(size_t)s2 * GV + lo + tid];
+            total += x;
+            if (s2 < sl) pre += x;
+            base += p.below[s2 * p.G + g];
+            nbad += p.bad[s2];
+        }
+    }
+
+    // exclusive scan of the per-id totals over the part
+    const uint32_t incl = wave_inclusive_scan(total, lane);
+    if (lane == 63) red[2 * kSortWaves + w] = incl;
+    __syncthreads();
+    uint32_t woff = 0;
+    for (int ww = 0; ww < w; ++ww) woff += red[2 * kSortWaves + ww];
+    const uint32_t rs = base + woff + incl - total;
+
+    if (sl == 0) {
+        if ((uint32_t)tid < span) {
+            p.count[lo + tid] = (int32_t)total;
+            p.row_start[lo + tid] = (int32_t)rs;
+            if (lo + tid == p.V - 1) {
+                p.row_start[p.V] = (int32_t)(rs + total);
+                *p.n_valid = (int32_t)(rs + total);
+            }
+        }
+        if (g == 0 && tid == 0) *p.n_bad = (int32_t)nbad;
+    }
+
+    // turn the per-wavefront counts into running positions
+    uint32_t o = rs + pre;
+#pragma unroll
+    for (int ww = 0; ww < kSortWaves; ++ww) {
+        const uint32_t c = cnt[ww][tid];
+        cnt[ww][tid] = o;
+        o += c;
+    }
+    __syncthreads();
+
+    // pass 2: same walk; every owned pair takes the next position of its id.
+    // Pairs of one id inside a tile are ranked by lane, tiles are walked in order
+    // and wavefronts own consecutive sub-slices: the sort is stable.
+    volatile uint32_t* my = cnt[w];
+    for_each_tile(sh, a, b, lane, [&](int j, int idx, bool valid, int32_t id) {
+        const uint32_t rel = (uint32_t)(id - lo);
+        const bool own = valid && rel < span;
+        uint64_t m = ballot64(own);
+        uint32_t pos = 0;
+        while (m) {
+            const int l = __builtin_ctzll(m);
+            const uint32_t r = bcast(rel, l);
+            const bool same = own && rel == r;
+            const uint64_t sm = ballot64(same);
+            const uint32_t bse = my[r];
+            if (same) pos = bse + lanes_below(sm);
+            if (lane == l) my[r] = bse + (uint32_t)__popcll(sm);
+            m &= ~sm;
+        }
+        if (own) {
+            p.perm[pos] = idx;
+            p.srt_id[pos] = id;
+            p.srt_addr[pos] = (uint64_t)(uintptr_t)sh.rows[j] + (uint64_t)(idx - sh.off[j]) * (uint64_t)p.row_bytes;
+        }
+    });
+}
+
+// ------------------------------------------------------------------ reduce
+struct ReduceParams {
+    int32_t V, d, C, ncb;
+    int32_t n_piece_items;      // pieces x column blocks
+    const int32_t* count;
+    const int32_t* row_start;
+    const int32_t* srt_id;
+    const uint64_t* srt_addr;
+    const int32_t* n_valid;
+    const float* dense_in;
+    float* dense_out;
+    float* partial;             // [2 * pieces][d]
+};
+
+template <typename RowT>
+__global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int item = blockIdx.x * 4 + wave;
+
+    if (item >= p.n_piece_items) {
+        // ---- copy item: one output row that received no pair
+        const int v = item - p.n_piece_items;
+        if (v >= p.V) return;
+        if (p.count[v] != 0) return;
+        const float* src = p.dense_in ? p.dense_in + (size_t)v * p.d : nullptr;
+        float* dst = p.dense_out + (size_t)v * p.d;
+        for (int c0 = 0; c0 < p.d; c0 += 4 * kColBlock) {
+            f4 x[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int col = c0 + u * kColBlock + lane * 4;
+                x[u] = (f4)(0.0f);
+                if (src && col < p.d) x[u] = load_f4(src + col);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int col = c0 + u * kColBlock + lane * 4;
+                if (col < p.d) store_f4(dst + col, x[u]);
+            }
+        }
+        return;
+    }
+
+    // ---- piece item: sorted positions [pos0, pos0 + C), columns [cb*256, cb*256 + 256)
+    const int k = item / p.ncb;
+    const int cb = item - k * p.ncb;
+    const int col = cb * kColBlock + lane * 4;
+    const bool colok = col < p.d;
+    const int C = p.C;
+    const int pos0 = k * C;
+    const int nvalid = *p.n_valid;
+    if (pos0 >= nvalid) return;
+
+    // lane j looks at sorted position pos0 + j; the window is two pieces long because
+    // an output row with at most C pairs that starts in this piece is finished here.
+    const int wpos = pos0 + lane;
+    const bool inwin = lane < 2 * C && wpos < nvalid;
+    int32_t id = -1, c = 0, s = 0;
+    uint64_t addr = 0;
+    if (inwin) {
+        id = p.srt_id[wpos];
+        addr = p.srt_addr[wpos];
+        c = p.count[id];
+        s = p.row_start[id];
+    }
+    const bool whole = c <= C;       // output row small enough to be summed by one item
+    const bool active = inwin && (whole ? (s >= pos0 && s < pos0 + C) : (lane < C));
+    const bool first = active && (wpos == s || (!whole && lane == 0));
+    const bool last = active && (wpos == s + c - 1 || (!whole && lane == C - 1));
+    const uint64_t A = ballot64(active);
+    const uint64_t F = ballot64(first);
+    const uint64_t Lm = ballot64(last);
+    const uint64_t W = ballot64(whole);
+    if (A == 0) return;
+    const int a = __builtin_ctzll(A);
+    const int b = 64 - __builtin_clzll(A);
+    const uint32_t slot = (uint32_t)(2 * k + (s >= pos0 ? 1 : 0));
+    const bool have_dense = p.dense_in != nullptr;
+
+    f4 acc = (f4)(0.0f);
+    for (int base = a; base < b; base += 8) {
+        f4 r[8], dn[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int j = base + u;
+            r[u] = (f4)(0.0f);
+            dn[u] = (f4)(0.0f);
+            if (j < b) {
+                const uint64_t ra = bcast64(addr, j);
+                if (colok) r[u] = load_row4<RowT>(ra, col);
+                if (have_dense && (((Lm & W) >> j) & 1ull)) {
+                    const int vj = (int)bcast((uint32_t)id, j);
+                    if (colok) dn[u] = load_f4(p.dense_in + (size_t)vj * p.d + col);
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int j = base + u;
+            if (j < b) {
+                const f4 prev = ((F >> j) & 1ull) ? (f4)(0.0f) : acc;
+                acc = prev + r[u];
+                if ((Lm >> j) & 1ull) {
+                    if ((W >> j) & 1ull) {
+                        const int vj = (int)bcast((uint32_t)id, j);
+                        if (colok) store_f4(p.dense_out + (size_t)vj * p.d + col, acc + dn[u]);
+                    } else {
+                        const uint32_t sj = bcast(slot, j);
+                        if (colok) store_f4(p.partial + (size_t)sj * p.d + col, acc);
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ combine
+struct CombineParams {
+    int32_t V, d, C, ncb;
+    const int32_t* count;
+    const int32_t* row_start;
+    const int32_t* srt_id;
+    const int32_t* n_valid;
+    const float* dense_in;
+    float* dense_out;
+    const float* partial;
+};
+
+__global__ __launch_bounds__(1024) void combine_kernel(CombineParams p)
+{
+    __shared__ f4 share[kSortWaves][64];
+
+    const int k = blockIdx.x;
+    const int C = p.C;
+    const int nvalid = *p.n_valid;
+    const int endpos = (k + 1) * C - 1;
+    if (endpos >= nvalid) return;
+    // the only output row that can start in piece k and be cut is the one that owns
+    // the piece's last position
+    const int v = p.srt_id[endpos];
+    const int c = p.count[v];
+    const int s = p.row_start[v];
+    if (c <= C || s < k * C) return;
+    const int P = (s + c - 1) / C - k + 1;      // pieces of this row, >= 2
+
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int cbw = min(p.ncb, kSortWaves);     // column blocks in flight
+    const int S = kSortWaves / cbw;             // shares per column block
+    const int cbi = w % cbw;
+    const int sh = w / cbw;
+    const int per = (P + S - 1) / S;
+    const int j0 = min(P, sh * per);
+    const int j1 = (sh < S) ? min(P, j0 + per) : j0;
+
+    for (int cb = cbi; cb - cbi < p.ncb; cb += cbw) {
+        const int col = cb * kColBlock + lane * 4;
+        const bool colok = cb < p.ncb && col < p.d;
+        f4 acc = (f4)(0.0f);
+        for (int jb = j0; jb < j1; jb += 8) {
+            f4 x[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int j = jb + u;
+                x[u] = (f4)(0.0f);
+                if (j < j1 && colok) {
+                    const size_t sl = (j == 0) ? (size_t)(2 * k + 1) : (size_t)(2 * (k + j));
+                    x[u] = load_f4(p.partial + sl * p.d + col);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (jb + u < j1) acc += x[u];
+        }
+        share[w][lane] = acc;
+        __syncthreads();
+        if (sh == 0 && colok) {
+            f4 tot = share[cbi][lane];
+            for (int q = 1; q < S; ++q)
+                if (q * per < P) tot += share[q * cbw + cbi][lane];
+            f4 dn = (f4)(0.0f);
+            if (p.dense_in) dn = load_f4(p.dense_in + (size_t)v * p.d + col);
+            store_f4(p.dense_out + (size_t)v * p.d + col, tot + dn);
+        }
+        __syncthreads();
+    }
+}
+
+// ------------------------------------------------------------------ unique ids (introspection)
+__global__ __launch_bounds__(1024) void unique_kernel(const int32_t* count, int V, int32_t* out,
+                                                      int32_t* n_out)
+{
+    __shared__ uint32_t wsum[kSortWaves];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = tid >> 6;
+    uint32_t base = 0;
+    for (int v0 = 0; v0 < V; v0 += 1024) {
+        const int v = v0 + tid;
+        const bool flag = v < V && count[v] > 0;
+        const uint64_t m = ballot64(flag);
+        if (lane == 0) wsum[w] = (uint32_t)__popcll(m);
+        __syncthreads();
+        uint32_t woff = 0, tot = 0;
+        for (int ww = 0; ww < kSortWaves; ++ww) {
+            if (ww < w) woff += wsum[ww];
+            tot += wsum[ww];
+        }
+        if (flag) out[base + woff + lanes_below(m)] = v;
+        base += tot;
+        __syncthreads();
+    }
+    if (tid == 0) *n_out = (int32_t)base;
+}
+
+// ------------------------------------------------------------------ host side
+struct Plan {
+    int32_t S, SL, G, C, NB, ncb;
+    size_t off_nvalid, off_nbad, off_count, off_row_start, off_perm, off_srt_id, off_srt_addr, off_tot,
+        off_below, off_bad, off_partial, total;
+};
+
+int g_piece_override = 0;
+void* g_ws = nullptr;
+int64_t g_ws_bytes = 0;
+Plan g_last_plan;
+int32_t g_last_V = 0;
+bool g_have_last = false;
+
+constexpr int kMaxProfile = 4096;
+hipEvent_t g_ev[2 * kMaxProfile];
+int g_ev_made = 0;
+int g_prof_cap = 0;
+int g_prof_used = 0;
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+int piece_tokens_for(int64_t n)
+{
+    if (g_piece_override) return g_piece_override;
+    return n <= kFusedSortMax ? 16 : 32;
+}
+
+void make_plan(int64_t n, int32_t d, int32_t V, Plan* pl)
+{
+    pl->G = (V + kPart - 1) / kPart;
+    if (n <= kFusedSortMax) {
+        pl->S = 1;
+        pl->SL = (int32_t)align_up((size_t)(n > 0 ? n : 1), 1024);
+    } else {
+        int64_t SL = kSliceTokens;
+        int64_t S = (n + SL - 1) / SL;
+        if (S > kMaxSlices) {
+            SL = (int64_t)align_up((size_t)((n + kMaxSlices - 1) / kMaxSlices), 1024);
+            S = (n + SL - 1) / SL;
+        }
+        pl->S = (int32_t)S;
+        pl->SL = (int32_t)SL;
+    }
+    pl->C = piece_tokens_for(n);
+    pl->NB = (int32_t)((n + pl->C - 1) / pl->C);
+    pl->ncb = (d + kColBlock - 1) / kColBlock;
+    size_t o = 0;
+    pl->off_nvalid = o;
+    pl->off_nbad = o + 4;
+    o = 256;
+    pl->off_count = o;
+    o = align_up(o + (size_t)V * 4, 256);
+    pl->off_row_start = o;
+    o = align_up(o + ((size_t)V + 1) * 4, 256);
+    pl->off_perm = o;
+    o = align_up(o + (size_t)n * 4, 256);
+    pl->off_srt_id = o;
+    o = align_up(o + (size_t)n * 4, 256);
+    pl->off_srt_addr = o;
+    o = align_up(o + (size_t)n * 8, 256);
+    pl->off_tot = o;
+    if (pl->S > 1) o = align_up(o + (size_t)pl->S * pl->G * kPart * 4, 256);
+    pl->off_below = o;
+    if (pl->S > 1) o = align_up(o + (size_t)pl->S * pl->G * 4, 256);
+    pl->off_bad = o;
+    if (pl->S > 1) o = align_up(o + (size_t)pl->S * 4, 256);
+    pl->off_partial = o;
+    o = align_up(o + (size_t)2 * pl->NB * (size_t)d * 4, 256);
+    pl->total = o;
+}
+
+int check_hip(hipError_t e) { return e == hipSuccess ? TS_OK : TS_ERR_HIP; }
+
+int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, int32_t V,
+                 const float* dense_in, float* dense_out, void* stream_v)
+{
+    Plan pl;
+    make_plan(n, d, V, &pl);
+    if (!g_ws || (int64_t)pl.total > g_ws_bytes) return TS_ERR_WORKSPACE;
+    if ((int64_t)pl.NB * pl.ncb + V >= ((int64_t)1 << 31) - 8) return TS_ERR_OVERFLOW;
+    hipStream_t stream = (hipStream_t)stream_v;
+    char* ws = (char*)g_ws;
+
+    SortParams sp;
+    sp.n = (int32_t)n;
+    sp.V = V;
+    sp.G = pl.G;
+    sp.S = pl.S;
+    sp.SL = pl.SL;
+    sp.row_bytes = d * (row_dtype == TS_ROW_BF16 ? 2 : 4);
+    sp.count = (int32_t*)(ws + pl.off_count);
+    sp.row_start = (int32_t*)(ws + pl.off_row_start);
+    sp.perm = (int32_t*)(ws + pl.off_perm);
+    sp.srt_id = (int32_t*)(ws + pl.off_srt_id);
+    sp.srt_addr = (uint64_t*)(ws + pl.off_srt_addr);
+    sp.tot = (uint32_t*)(ws + pl.off_tot);
+    sp.below = (uint32_t*)(ws + pl.off_below);
+    sp.bad = (uint32_t*)(ws + pl.off_bad);
+    sp.n_valid = (int32_t*)(ws + pl.off_nvalid);
+    sp.n_bad = (int32_t*)(ws + pl.off_nbad);
+
+    const dim3 sgrid((unsigned)pl.G, (unsigned)pl.S);
+    if (pl.S == 1) {
+        hipLaunchKernelGGL(sort_kernel<SORT_FUSED>, sgrid, dim3(1024), 0, stream, sp, sh);
+    } else {
+        hipLaunchKernelGGL(sort_kernel<SORT_COUNT>, sgrid, dim3(1024), 0, stream, sp, sh);
+        hipLaunchKernelGGL(sort_kernel<SORT_SCATTER>, sgrid, dim3(1024), 0, stream, sp, sh);
+    }
+    if (hipGetLastError() != hipSuccess) return TS_ERR_HIP;
+
+    ReduceParams rp;
+    rp.V = V;
+    rp.d = d;
+    rp.C = pl.C;
+    rp.ncb = pl.ncb;
+    rp.n_piece_items = pl.NB * pl.ncb;
+    rp.count = sp.count;
+    rp.row_start = sp.row_start;
+    rp.srt_id = sp.srt_id;
+    rp.srt_addr = sp.srt_addr;
+    rp.n_valid = sp.n_valid;
+    rp.dense_in = dense_in;
+    rp.dense_out = dense_out;
+    rp.partial = (float*)(ws + pl.off_partial);
+    const bool in_place = dense_in == dense_out;
+    const int64_t items = (int64_t)rp.n_piece_items + (in_place ? 0 : V);
+    const unsigned rgrid = (unsigned)((items + 3) / 4);
+
+    const bool prof = g_prof_used < g_prof_cap;
+    if (prof && hipEventRecord(g_ev[2 * g_prof_used], stream) != hipSuccess) return TS_ERR_HIP;
+    if (rgrid > 0) {
+        if (row_dtype == TS_ROW_BF16)
+            hipLaunchKernelGGL(reduce_kernel<uint16_t>, dim3(rgrid), dim3(256), 0, stream, rp);
+        else
+            hipLaunchKernelGGL(reduce_kernel<float>, dim3(rgrid), dim3(256), 0, stream, rp);
+    }
+    if (prof) {
+        if (hipEventRecord(g_ev[2 * g_prof_used + 1], stream) != hipSuccess) return TS_ERR_HIP;
+        ++g_prof_used;
+    }
+    if (hipGetLastError() != hipSuccess) return TS_ERR_HIP;
+
+    if (pl.NB > 0) {
+        CombineParams cp;
+        cp.V = V;
+        cp.d = d;
+        cp.C = pl.C;
+        cp.ncb = pl.ncb;
+        cp.count = sp.count;
+        cp.row_start = sp.row_start;
+        cp.srt_id = sp.srt_id;
+        cp.n_valid = sp.n_valid;
+        cp.dense_in = dense_in;
+        cp.dense_out = dense_out;
+        cp.partial = rp.partial;
+        hipLaunchKernelGGL(combine_kernel, dim3((unsigned)pl.NB), dim3(1024), 0, stream, cp);
+        if (hipGetLastError() != hipSuccess) return TS_ERR_HIP;
+    }
+    g_last_plan = pl;
+    g_last_V = V;
+    g_have_last = true;
+    return TS_OK;
+}
+
+int validate_common(int64_t n_total, int32_t d, int32_t V, const float* dense_in, float* dense_out)
+{
+    if (!dense_out) return TS_ERR_NULL;
+    if (n_total < 0 || V <= 0 || d <= 0 || (d % 4) != 0) return TS_ERR_SHAPE;
+    if (n_total >= ((int64_t)1 << 31)) return TS_ERR_OVERFLOW;
+    if (((uintptr_t)dense_out & 15u) || ((uintptr_t)dense_in & 15u)) return TS_ERR_ALIGN;
+    return TS_OK;
+}
+
+int densify_shards(const int32_t* const* ids_k, const void* const* rows_k, const int64_t* n_k, int32_t k,
+                   int32_t row_dtype, int32_t d, int32_t V, const float* dense_in, float* dense_out,
+                   void* stream)
+{
+    if (k < 1 || k > TS_MAX_SHARDS) return TS_ERR_SHAPE;
+    if (row_dtype != TS_ROW_FP32 && row_dtype != TS_ROW_BF16) return TS_ERR_SHAPE;
+    if (!ids_k || !rows_k || !n_k) return TS_ERR_NULL;
+    int64_t n_total = 0;
+    for (int j = 0; j < k; ++j) {
+        if (n_k[j] < 0) return TS_ERR_SHAPE;
+        n_total += n_k[j];
+        if (n_total >= ((int64_t)1 << 31)) return TS_ERR_OVERFLOW;
+    }
+    int rc = validate_common(n_total, d, V, dense_in, dense_out);
+    if (rc != TS_OK) return rc;
+    ShardTable sh;
+    memset(&sh, 0, sizeof sh);
+    sh.k = k;
+    int64_t off = 0;
+    for (int j = 0; j < k; ++j) {
+        if (n_k[j] > 0 && (!ids_k[j] || !rows_k[j])) return TS_ERR_NULL;
+        if ((uintptr_t)rows_k[j] & 15u) return TS_ERR_ALIGN;
+        if ((uintptr_t)ids_k[j] & 3u) return TS_ERR_ALIGN;
+        sh.off[j] = (int32_t)off;
+        sh.ids[j] = ids_k[j];
+        sh.rows[j] = (const char*)rows_k[j];
+        off += n_k[j];
+    }
+    for (int j = k; j <= TS_MAX_SHARDS; ++j) sh.off[j] = (int32_t)off;
+    return densify_impl(sh, n_total, row_dtype, d, V, dense_in, dense_out, stream);
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ C ABI
+extern "C" {
+
+int ts_densify(const int32_t* ids, const float* rows, int64_t n, int32_t d, int32_t V,
+               const float* dense_in, float* dense_out, void* stream)
+{
+    const void* r = rows;
+    return densify_shards(&ids, &r, &n, 1, TS_ROW_FP32, d, V, dense_in, dense_out, stream);
+}
+
+int ts_densify_bf16(const int32_t* ids, const uint16_t* rows, int64_t n, int32_t d, int32_t V,
+                    const float* dense_in, float* dense_out, void* stream)
+{
+    const void* r = rows;
+    return densify_shards(&ids, &r, &n, 1, TS_ROW_BF16, d, V, dense_in, dense_out, stream);
+}
+
+int ts_densify_multi(const int32_t* const* ids_k, const void* const* rows_k, const int64_t* n_k,
+                     int32_t k, int32_t row_dtype, int32_t d, int32_t V, const float* dense_in,
+                     float* dense_out, void* stream)
+{
+    return densify_shards(ids_k, rows_k, n_k, k, row_dtype, d, V, dense_in, dense_out, stream);
+}
+
+int ts_buffer_bytes(int64_t k, int64_t N, int32_t d, int32_t V, int32_t row_dtype, int64_t* gathered_bytes,
+                    int64_t* dense_bytes)
+{
+    if (!gathered_bytes || !dense_bytes) return TS_ERR_NULL;
+    if (k < 0 || N < 0 || d <= 0 || V <= 0) return TS_ERR_SHAPE;
+    if (row_dtype != TS_ROW_FP32 && row_dtype != TS_ROW_BF16) return TS_ERR_SHAPE;
+    const int64_t elem = row_dtype == TS_ROW_BF16 ? 2 : 4;
+    int64_t per_slice, kn, g, dn;
+    if (__builtin_mul_overflow(elem, (int64_t)d, &per_slice) || __builtin_add_overflow(per_slice, (int64_t)4, &per_slice) ||
+        __builtin_mul_overflow(k, N, &kn) || __builtin_mul_overflow(kn, per_slice, &g) ||
+        __builtin_mul_overflow((int64_t)4 * V, (int64_t)d, &dn))
+        return TS_ERR_OVERFLOW;
+    *gathered_bytes = g;
+    *dense_bytes = dn;
+    return TS_OK;
+}
+
+int ts_workspace_bytes(int64_t n_total, int32_t d, int32_t V, int64_t* bytes)
+{
+    if (!bytes) return TS_ERR_NULL;
+    if (n_total < 0 || V <= 0 || d <= 0 || (d % 4) != 0) return TS_ERR_SHAPE;
+    if (n_total >= ((int64_t)1 << 31)) return TS_ERR_OVERFLOW;
+    Plan a, b;
+    make_plan(n_total, d, V, &a);
+    make_plan(n_total < kFusedSortMax ? n_total : kFusedSortMax, d, V, &b);
+    *bytes = (int64_t)(a.total > b.total ? a.total : b.total);
+    return TS_OK;
+}
+
+int ts_bind_workspace(void* ws, int64_t bytes)
+{
+    if (!ws) {
+        g_ws = nullptr;
+        g_ws_bytes = 0;
+        g_have_last = false;
+        return TS_OK;
+    }
+    if (bytes <= 0) return TS_ERR_SHAPE;
+    if ((uintptr_t)ws & 255u) return TS_ERR_ALIGN;
+    g_ws = ws;
+    g_ws_bytes = bytes;
+    g_have_last = false;
+    return TS_OK;
+}
+
+int ts_last_views(const int32_t** count, const int32_t** row_start, const int32_t** perm,
+                  const int32_t** n_valid, const int32_t** n_bad_ids)
+{
+    if (!g_ws || !g_have_last) return TS_ERR_WORKSPACE;
+    const char* ws = (const char*)g_ws;
+    if (count) *count = (const int32_t*)(ws + g_last_plan.off_count);
+    if (row_start) *row_start = (const int32_t*)(ws + g_last_plan.off_row_start);
+    if (perm) *perm = (const int32_t*)(ws + g_last_plan.off_perm);
+    if (n_valid) *n_valid = (const int32_t*)(ws + g_last_plan.off_nvalid);
+    if (n_bad_ids) *n_bad_ids = (const int32_t*)(ws + g_last_plan.off_nbad);
+    return TS_OK;
+}
+
+int ts_unique_ids(int32_t* unique_ids_out, int32_t* n_unique_out, void* stream)
+{
+    if (!unique_ids_out || !n_unique_out) return TS_ERR_NULL;
+    if (!g_ws || !g_have_last) return TS_ERR_WORKSPACE;
+    const int32_t* count = (const int32_t*)((const char*)g_ws + g_last_plan.off_count);
+    hipLaunchKernelGGL(unique_kernel, dim3(1), dim3(1024), 0, (hipStream_t)stream, count, g_last_V,
+                       unique_ids_out, n_unique_out);
+    return check_hip(hipGetLastError());
+}
+
+int ts_profile_begin(int32_t capacity)
+{
+    if (capacity < 0 || capacity > kMaxProfile) return TS_ERR_SHAPE;
+    while (g_ev_made < 2 * capacity) {
+        if (hipEventCreate(&g_ev[g_ev_made]) != hipSuccess) return TS_ERR_HIP;
+        ++g_ev_made;
+    }
+    g_prof_cap = capacity;
+    g_prof_used = 0;
+    return TS_OK;
+}
+
+int ts_profile_end(float* ms_out, int32_t capacity, int32_t* n_out)
+{
+    if (!ms_out || !n_out) return TS_ERR_NULL;
+    int m = g_prof_used < capacity ? g_prof_used : capacity;
+    if (m < 0) m = 0;
+    for (int i = 0; i < m; ++i) {
+        if (hipEventSynchronize(g_ev[2 * i + 1]) != hipSuccess) return TS_ERR_HIP;
+        if (hipEventElapsedTime(&ms_out[i], g_ev[2 * i], g_ev[2 * i + 1]) != hipSuccess) return TS_ERR_HIP;
+    }
+    *n_out = m;
+    g_prof_cap = 0;
+    g_prof_used = 0;
+    return TS_OK;
+}
+
+int ts_set_piece_tokens(int32_t piece_tokens)
+{
+    if (piece_tokens != 0 && piece_tokens != 8 && piece_tokens != 16 && piece_tokens != 32) return TS_ERR_SHAPE;
+    g_piece_override = piece_tokens;
+    return TS_OK;
+}
+
+const char* ts_status_string(int status)
+{
+    switch (status) {
+        case TS_OK: return "ok";
+        case TS_ERR_NULL: return "a required pointer is NULL";
+        case TS_ERR_SHAPE: return "bad shape or argument value";
+        case TS_ERR_ALIGN: return "pointer not aligned";
+        case TS_ERR_WORKSPACE: return "workspace not bound or too small";
+        case TS_ERR_HIP: return "HIP runtime error";
+        case TS_ERR_OVERFLOW: return "size overflow";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

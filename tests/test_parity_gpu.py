@@ -1,0 +1,187 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU checker, element by element,
+on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1905_04035_amd import binding as ts
+from paper_1905_04035_amd import workloads as wl
+
+from parity import TOL, check, run_gpu, run_oracle, to_dev, DEV
+
+pytestmark = pytest.mark.gpu
+
+
+def _case(w, **kw):
+    dense = kw.pop("dense", True)
+    exact_bits = kw.pop("exact_bits", False)
+    g = run_gpu(w, dense=dense, **kw)
+    r = run_oracle(w, dense=dense)
+    return check(g, r, w, exact_bits=exact_bits), g, r
+
+
+# ------------------------------------------------------------- the named configurations
+def test_tiny_config():
+    worst, g, r = _case(wl.make("tiny"))
+    assert len(g["unique_ids"]) > 800
+    assert worst < TOL
+
+
+def test_transformer_base_share_single_and_multi():
+    w = wl.make("transformer_base")
+    _case(w, mode="single")
+    _case(w, mode="multi")
+
+
+def test_transformer_big_share():
+    w = wl.make("transformer_big")
+    worst, g, r = _case(w, mode="single")
+    assert g["count"].max() > 1500          # the hot row is cut into many pieces
+    _case(w, mode="multi")
+
+
+def test_large_batch_bf16_rows():
+    w = wl.make("large_batch_bf16")
+    _case(w, mode="multi")
+
+
+def test_multi_shard_stress_and_buffer_bytes():
+    w = wl.make("multi_shard_stress")
+    worst, g, r = _case(w, mode="multi", group=2)        # 16 shards of encoder + decoder rows
+    assert g["count"].max() > 0.3 * w.n_total             # one row takes about 38 % of the pairs
+    top10 = np.sort(g["count"])[-10:].sum() / w.n_total
+    assert top10 > 0.7
+    gathered, dense = ts.ts_buffer_bytes(16, 2 * 8192, w.d, w.V)
+    assert (gathered, dense) == (1074790400, 134217728)
+    assert (gathered, dense) == oracle.buffer_bytes(16, 2 * 8192, w.d, w.V)
+
+
+# ------------------------------------------------------------- exact pins on the GPU path
+@pytest.mark.parametrize("name", ["distinct", "zipf", "single"])
+def test_small_integer_values_are_bit_exact(name):
+    n = {"distinct": 3000, "zipf": 20000, "single": 5000}[name]
+    w = wl.make_custom(V=5000, d=256, n_list=[n], ids=name, zipf_s=1.3, seed=21, integer_values=True)
+    _case(w, exact_bits=True)
+
+
+def test_all_distinct_ids_bit_exact_on_normal_data():
+    w = wl.make_custom(V=4096, d=512, n_list=[3000], ids="distinct", seed=22)
+    _case(w, exact_bits=True)
+
+
+def test_one_row_takes_every_pair_across_slices():
+    # 40000 pairs: more than one sort slice, every pair on one row, 1250+ pieces to combine
+    w = wl.make_custom(V=3000, d=128, n_list=[25000, 15000], ids="single", seed=23, integer_values=True)
+    _case(w, exact_bits=True, mode="multi")
+    wf = wl.make_custom(V=3000, d=128, n_list=[25000, 15000], ids="single", seed=23)
+    _case(wf, mode="multi")
+
+
+# ------------------------------------------------------------- shapes and edges
+@pytest.mark.parametrize("V,d,n", [(1, 4, 10), (7, 4, 0), (1000, 64, 2048), (1025, 260, 999),
+                                   (2049, 1024, 65), (33000, 8, 70000), (300, 2048, 513)])
+def test_ragged_shapes(V, d, n):
+    w = wl.make_custom(V=V, d=d, n_list=[n], ids="zipf", zipf_s=1.2, seed=V + d + n)
+    _case(w)
+
+
+@pytest.mark.parametrize("piece", [8, 16, 32])
+def test_piece_sizes_and_exact_boundaries(piece):
+    ts.ts_set_piece_tokens(piece)
+    try:
+        # rows with exactly piece-1, piece, piece+1 and 2*piece pairs, at shifting offsets
+        V, d = 64, 256
+        counts = [piece - 1, piece, piece + 1, 2 * piece, 1, 2 * piece + 1, 3, piece]
+        ids = np.concatenate([np.full(c, 5 + 3 * i, dtype=np.int32) for i, c in enumerate(counts)])
+        rng = np.random.default_rng(piece)
+        ids = ids[rng.permutation(len(ids))]
+        rows = rng.integers(-4, 5, size=(len(ids), d)).astype(np.float32)
+        dense = rng.integers(-4, 5, size=(V, d)).astype(np.float32)
+        w = wl.Workload(spec=wl.Spec("custom", -1, V, d, 1, 0, "zipf"), ids=[ids], rows=[rows], dense_in=dense)
+        _case(w, exact_bits=True)
+        _case(wl.make_custom(V=2000, d=512, n_list=[9000], zipf_s=1.4, seed=31))
+    finally:
+        ts.ts_set_piece_tokens(0)
+
+
+def test_no_dense_operand_and_in_place():
+    w = wl.make_custom(V=3000, d=256, n_list=[5000, 1000], seed=41)
+    _case(w, dense=False)                     # Listing 1 alone: untouched rows are +0.0
+    _case(w, in_place=True)                   # dense_out == dense_in
+
+
+def test_out_of_range_ids_are_skipped_and_counted():
+    w = wl.make_custom(V=500, d=64, n_list=[4000], seed=42)
+    ids = w.ids[0]
+    ids[::7] = -1
+    ids[3::11] = 500
+    ids[5::13] = np.iinfo(np.int32).max
+    ids[6::17] = np.iinfo(np.int32).min
+    worst, g, r = _case(w)
+    assert g["n_bad"] == r.n_bad > 1000
+
+
+def test_untouched_rows_keep_special_bit_patterns():
+    w = wl.make_custom(V=100, d=64, n_list=[30], ids="distinct", seed=43)
+    bits = w.dense_in.view(np.uint32)
+    bits[:, 0] = 0x80000000
+    bits[:, 1] = 0x7FC12345
+    bits[:, 2] = 0xFF800000
+    g = run_gpu(w)
+    r = run_oracle(w)
+    untouched = r.count == 0
+    assert np.array_equal(g["out"][untouched].view(np.uint32), w.dense_in[untouched].view(np.uint32))
+    assert np.array_equal(np.isnan(g["out"]), np.isnan(r.out))
+
+
+def test_empty_and_ragged_shards():
+    w = wl.make_custom(V=900, d=128, n_list=[0, 70, 0, 1, 64, 129, 0], seed=44)
+    _case(w, mode="multi")
+    # pointers into one buffer == the buffer itself
+    ids, rows = w.concatenated()
+    a = run_gpu(w, mode="multi")
+    b = run_gpu(w, mode="single")
+    assert np.array_equal(a["out"].view(np.uint32), b["out"].view(np.uint32))
+    assert np.array_equal(a["perm"], b["perm"])
+
+
+def test_runs_are_bit_identical():
+    w = wl.make("transformer_base")
+    a = run_gpu(w, mode="single")
+    b = run_gpu(w, mode="single")
+    c = run_gpu(w, mode="multi")
+    assert np.array_equal(a["out"].view(np.uint32), b["out"].view(np.uint32))
+    assert np.array_equal(a["out"].view(np.uint32), c["out"].view(np.uint32))
+
+
+def test_dense_gradient_fed_as_slices():
+    w = wl.make_custom(V=700, d=64, n_list=[1500], seed=45)
+    fused = run_gpu(w)
+    w2 = wl.Workload(spec=w.spec, ids=[np.arange(w.V, dtype=np.int32)] + w.ids,
+                     rows=[w.dense_in] + w.rows, dense_in=w.dense_in)
+    sliced = run_gpu(w2, mode="multi", dense=False)
+    r = run_oracle(w)
+    assert np.all(np.abs(sliced["out"].astype(np.float64) - r.exact) <= TOL * r.abs_sum)
+    assert np.array_equal(sliced["count"], fused["count"] + 1)
+
+
+def test_error_codes_from_the_host_checks():
+    V, d = 16, 8
+    out = torch.zeros((V, d), dtype=torch.float32, device=DEV)
+    ids = torch.zeros(4, dtype=torch.int32, device=DEV)
+    rows = torch.zeros((4, d), dtype=torch.float32, device=DEV)
+    ts.ts_bind_workspace(None)
+    assert ts.ts_densify_raw(ids.data_ptr(), rows.data_ptr(), 4, d, V, None, out.data_ptr()) == ts.TS_ERR_WORKSPACE
+    ws = ts.Workspace(4, d, V, DEV)
+    try:
+        assert ts.ts_densify_raw(ids.data_ptr(), rows.data_ptr(), 4, d, V, None, out.data_ptr()) == ts.TS_OK
+        assert ts.ts_densify_raw(ids.data_ptr(), rows.data_ptr(), 100000, d, V, None, out.data_ptr()) == ts.TS_ERR_WORKSPACE
+        assert ts.ts_densify_raw(None, rows.data_ptr(), 4, d, V, None, out.data_ptr()) == ts.TS_ERR_NULL
+        assert ts.ts_densify_raw(ids.data_ptr(), rows.data_ptr(), 4, d, V, None, None) == ts.TS_ERR_NULL
+        assert ts.ts_densify_raw(ids.data_ptr(), rows.data_ptr(), -1, d, V, None, out.data_ptr()) == ts.TS_ERR_SHAPE
+        assert ts.ts_densify_raw(ids.data_ptr(), rows.data_ptr(), 4, 6, V, None, out.data_ptr()) == ts.TS_ERR_SHAPE
+        assert ts.ts_densify_raw(ids.data_ptr(), rows.data_ptr() + 4, 4, d, V, None, out.data_ptr()) == ts.TS_ERR_ALIGN
+        torch.cuda.synchronize()
+    finally:
+        ws.close()
