@@ -1,0 +1,184 @@
+#!/usr/bin/env python3
+"""Benchmark of the densify hot path on one MI355X.
+
+A step is one whole ts_densify call (sort, row reduce with the dense add fused,
+combine of cut rows) on the transformer-big worker share: V=32768, d=1024, fp32,
+encoder + decoder contributions of 8192 rows each laid end to end (n=16384), ids
+Zipf(1.1).  Inputs are resident in HBM before the timed region; the calls rotate
+over several independent buffer sets so that no call finds its lines in the
+memory-side cache.
+
+Prints ONE JSON line: whole-call throughput in algorithmic GB/s (`value`), the
+roofline of the dominant kernel measured with HIP events inside the same timed
+region, and the CPU checker timed on the host as a baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def algorithmic_bytes(n, d, V, elem):
+    """Read dense_in, write dense_out, read every id and value row once."""
+    return 2 * 4 * V * d + n * (4 + elem * d)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--workload", default="transformer_big",
+                    choices=["transformer_base", "transformer_big", "large_batch_bf16", "multi_shard_stress"])
+    ap.add_argument("--sets", type=int, default=3, help="independent buffer sets to rotate over")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-events", action="store_true",
+                    help="do not record per-kernel HIP events inside the timed region")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_1905_04035_amd import binding as ts
+    from paper_1905_04035_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    ts.lib()      # fail loudly if the HIP library has not been built
+
+    w = wl.make(args.workload)
+    V, d, n = w.V, w.d, w.n_total
+    elem = 2 if w.row_dtype == wl.ROW_BF16 else 4
+    multi = args.workload == "multi_shard_stress"
+    ids_h, rows_h = w.concatenated()
+
+    def dev_rows(a):
+        return torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).to(dev)
+
+    sets = []
+    for _ in range(args.sets):
+        s = dict(dense_in=torch.from_numpy(w.dense_in).to(dev),
+                 dense_out=torch.empty((V, d), dtype=torch.float32, device=dev))
+        if multi:
+            ik, rk = w.grouped(2)
+            s["ids"] = [torch.from_numpy(i).to(dev) for i in ik]
+            s["rows"] = [dev_rows(r) for r in rk]
+        else:
+            s["ids"] = torch.from_numpy(ids_h).to(dev)
+            s["rows"] = dev_rows(rows_h)
+        sets.append(s)
+    ws = ts.Workspace(n, d, V, dev)
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        s = sets[i % len(sets)]
+        if multi:
+            ts.ts_densify_multi(s["ids"], s["rows"], w.row_dtype, d, V, s["dense_in"], s["dense_out"], stream)
+        elif w.row_dtype == wl.ROW_BF16:
+            ts.ts_densify_bf16(s["ids"], s["rows"], d, V, s["dense_in"], s["dense_out"], stream)
+        else:
+            ts.ts_densify(s["ids"], s["rows"], d, V, s["dense_in"], s["dense_out"], stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    use_events = not args.no_events and args.steps <= 4096
+    if use_events:
+        ts.ts_profile_begin(args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kernel_ms = ts.ts_profile_end(args.steps) if use_events else []
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    alg = algorithmic_bytes(n, d, V, elem)
+    gbps = alg / (ms_per_step * 1e-3) / 1e9
+    rows_per_s = n / (ms_per_step * 1e-3)
+
+    # parity of a timed output against the CPU checker (test infrastructure, used here to
+    # vouch for the timed numbers and as the reported CPU baseline)
+    import oracle
+    r = oracle.densify(w.ids, w.rows, d, V, w.dense_in, w.row_dtype)
+    out = sets[(args.steps - 1) % len(sets)]["dense_out"].cpu().numpy()
+    err = np.abs(out.astype(np.float64) - r.exact)
+    parity_ok = bool(np.all(err <= 1e-5 * r.abs_sum))
+
+    # the row-reduce kernel: everything except the ids (read by the sort) and the dense
+    # in/out traffic of rows that are cut into pieces (moved by the combine kernel)
+    C = 16 if n <= 32768 else 32
+    n_cut = int((r.count > C).sum())
+    alg_reduce = n * elem * d + 2 * 4 * d * (V - n_cut)
+    roofline = None
+    if kernel_ms:
+        k_ms = float(np.mean(kernel_ms))
+        ach = alg_reduce / (k_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "reduce_kernel", "achieved": round(ach, 1),
+                    "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4),
+                    "traffic": None, "avg_kernel_us": round(k_ms * 1e3, 2),
+                    "median_kernel_us": round(float(np.median(kernel_ms)) * 1e3, 2),
+                    "algorithmic_bytes_per_launch": alg_reduce}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        t_one = oracle.densify_timed(ids_h, rows_h, d, V, w.dense_in, w.row_dtype, repeats=1)[0]
+        reps = int(min(40, max(3, round(15.0 / max(t_one, 1e-3)))))
+        times = oracle.densify_timed(ids_h, rows_h, d, V, w.dense_in, w.row_dtype, repeats=reps)
+        t_med = float(np.median(times))
+        cpu = {"value": round(alg / t_med / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+               "sample": f"the whole {args.workload} call (n={n} pairs), median of {reps} runs after one warm-up",
+               "ms_per_call": round(t_med * 1e3, 2), "rows_per_s": round(n / t_med, 1),
+               "host_cores_available": os.cpu_count()}
+
+    gathered, dense_b = ts.ts_buffer_bytes(16 if multi else 1, n // (16 if multi else 1), d, V, w.row_dtype)
+    line = {
+        "metric": "densify throughput (algorithmic HBM GB/s of the whole ts_densify call)",
+        "value": round(gbps, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if elem == 4 else "bf16 rows, f32 sums",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "V": V, "d": d, "n_pairs": n,
+                   "ids": f"zipf(s={w.spec.zipf_s}) over V, random rank->id permutation",
+                   "buffer_sets": len(sets), "entry_point": "ts_densify_multi" if multi else
+                   ("ts_densify_bf16" if elem == 2 else "ts_densify")},
+        "pct_of_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
+        "rows_per_s": round(rows_per_s, 1),
+        "algorithmic_bytes_per_step": alg,
+        "unique_ids": int((r.count > 0).sum()),
+        "max_count": int(r.count.max()),
+        "gathered_vs_dense_bytes": [gathered, dense_b],
+        "parity_ok": parity_ok,
+        "events_in_timed_region": bool(use_events),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    ws.close()
+    print(json.dumps(line))
+    if not parity_ok:
+        sys.exit(1)
+
+
+if __name__ == "__main__":
+    main()
