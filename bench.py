@@ -39,6 +39,11 @@ def main():
                     choices=["transformer_base", "transformer_big", "large_batch_bf16", "multi_shard_stress"])
     ap.add_argument("--sets", type=int, default=3, help="independent buffer sets to rotate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--overlap-mib", type=float, default=-1.0,
+                    help="dense bytes copied beside each sort launch (tuning; -1 = library default)")
+    ap.add_argument("--overlap-combine-mib", type=float, default=-1.0, help="tuning; -1 = library default")
+    ap.add_argument("--stagger", type=int, nargs=2, default=None, metavar=("WGS", "SLEEPS"), help="tuning")
+    ap.add_argument("--piece-tokens", type=int, default=0, help="tuning; 0 = library default")
     ap.add_argument("--no-events", action="store_true",
                     help="do not record per-kernel HIP events inside the timed region")
     args = ap.parse_args()
@@ -57,6 +62,13 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     ts.lib()      # fail loudly if the HIP library has not been built
+    if args.overlap_mib >= 0 or args.overlap_combine_mib >= 0:
+        ts.ts_set_overlap_bytes(int(args.overlap_mib * (1 << 20)) if args.overlap_mib >= 0 else -1,
+                                int(args.overlap_combine_mib * (1 << 20)) if args.overlap_combine_mib >= 0 else -1)
+    if args.stagger:
+        ts.ts_set_stagger(args.stagger[0], args.stagger[1])
+    if args.piece_tokens:
+        ts.ts_set_piece_tokens(args.piece_tokens)
 
     w = wl.make(args.workload)
     V, d, n = w.V, w.d, w.n_total
@@ -95,18 +107,31 @@ def main():
         step(i)
     torch.cuda.synchronize()
 
-    use_events = not args.no_events and args.steps <= 4096
-    if use_events:
-        ts.ts_profile_begin(args.steps)
-    torch.cuda.synchronize()
+    # timed region: exactly `steps` calls, nothing else on the stream
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(i)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    kernel_ms = ts.ts_profile_end(args.steps) if use_events else []
-
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    info = ts.ts_last_launch_info()
+
+    # the same `steps` calls again, now with a HIP event pair recorded by the library around
+    # every launch of the row-reduce kernel on the stream it runs on.  Kept out of the region
+    # above because the extra event packets lengthen a whole call by several microseconds.
+    use_events = not args.no_events and args.steps <= 4096
+    kernel_ms = []
+    ms_per_step_with_events = None
+    if use_events:
+        ts.ts_profile_begin(args.steps)
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for i in range(args.steps):
+            step(i)
+        torch.cuda.synchronize()
+        ms_per_step_with_events = (time.perf_counter() - t2) * 1e3 / args.steps
+        kernel_ms = ts.ts_profile_end(args.steps)
+
     alg = algorithmic_bytes(n, d, V, elem)
     gbps = alg / (ms_per_step * 1e-3) / 1e9
     rows_per_s = n / (ms_per_step * 1e-3)
@@ -119,11 +144,16 @@ def main():
     err = np.abs(out.astype(np.float64) - r.exact)
     parity_ok = bool(np.all(err <= 1e-5 * r.abs_sum))
 
-    # the row-reduce kernel: everything except the ids (read by the sort) and the dense
-    # in/out traffic of rows that are cut into pieces (moved by the combine kernel)
-    C = 16 if n <= 32768 else 32
-    n_cut = int((r.count > C).sum())
-    alg_reduce = n * elem * d + 2 * 4 * d * (V - n_cut)
+    # Algorithmic bytes of one launch of the row-reduce kernel: every value row once; dense_in
+    # read and dense_out written for each output row it finishes itself (1..C pairs) and for
+    # each untouched row of the range it copies.  Rows cut into pieces (more than C pairs) get
+    # their dense traffic in the combine kernel; the other untouched rows are copied beside the
+    # sort and the combine launches; ids are read by the sort.
+    C = info["piece_tokens"]
+    x0, x1 = info["sort_copy_rows_end"], info["reduce_copy_rows_end"]
+    whole = int(((r.count > 0) & (r.count <= C)).sum())
+    untouched_mid = int((r.count[x0:x1] == 0).sum())
+    alg_reduce = n * elem * d + 2 * 4 * d * (whole + untouched_mid)
     roofline = None
     if kernel_ms:
         k_ms = float(np.mean(kernel_ms))
@@ -132,7 +162,10 @@ def main():
                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4),
                     "traffic": None, "avg_kernel_us": round(k_ms * 1e3, 2),
                     "median_kernel_us": round(float(np.median(kernel_ms)) * 1e3, 2),
-                    "algorithmic_bytes_per_launch": alg_reduce}
+                    "algorithmic_bytes_per_launch": alg_reduce,
+                    "share_of_call_bytes": round(alg_reduce / alg, 4),
+                    "measured": "HIP events around every reduce_kernel launch in a second pass of the same steps",
+                    "ms_per_step_with_events": round(ms_per_step_with_events, 5)}
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -170,7 +203,7 @@ def main():
         "max_count": int(r.count.max()),
         "gathered_vs_dense_bytes": [gathered, dense_b],
         "parity_ok": parity_ok,
-        "events_in_timed_region": bool(use_events),
+        "launch_split": info,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

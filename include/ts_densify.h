@@ -115,6 +115,16 @@ int ts_last_views(const int32_t** count, const int32_t** row_start, const int32_
                   const int32_t** n_valid, const int32_t** n_bad_ids);
 
 /*
+ * How the most recent call was split over its launches, for byte accounting in
+ * benchmarks.  Writes 8 int32 to info (host): [0] piece_tokens C; [1] X: dense rows
+ * [0, X) were copied beside the sort launches; [2] T: untouched rows in [X, T) were
+ * copied by the row-reduce kernel, those in [T, V) beside the combine launch;
+ * [3] sort slices; [4] ids per sort work-group; [5] pieces; [6] combine work-groups per
+ * column block; [7] 1 if the call was in place.
+ */
+int ts_last_launch_info(int32_t* info);
+
+/*
  * Ascending list of the rows that received at least one pair in the most recent
  * call: writes unique_ids_out[0 .. n_unique) (device, capacity >= min(n, V)
  * int32) and *n_unique_out (device int32).  Enqueues one small kernel.
@@ -137,6 +147,25 @@ int ts_profile_end(float* ms_out, int32_t capacity, int32_t* n_out);
  * summation order (still deterministic) and the workspace size.
  */
 int ts_set_piece_tokens(int32_t piece_tokens);
+
+/*
+ * Tuning.  The sort and the combine launches are latency-bound, so work-groups that copy
+ * dense rows run beside them to keep HBM busy.  sort_bytes: dense bytes (read + write)
+ * copied from dense_in to dense_out beside each sort launch, before it is known which
+ * rows receive pairs (those are overwritten afterwards).  combine_bytes: the same beside
+ * the combine launch (untouched rows only).  -1 = default, 0 = none.  ts_set_stagger
+ * makes the first `work_groups` copying work-groups of a sort launch wait `sleeps` x 0.85
+ * microseconds, so that the sort's own first loads are not queued behind the copy.
+ * Results do not depend on any of these.
+ */
+int ts_set_overlap_bytes(int64_t sort_bytes, int64_t combine_bytes);
+int ts_set_stagger(int32_t work_groups, int32_t sleeps);
+
+/* Tuning.  Ids owned by one sort work-group (64 .. 1024, power of two; 0 = choose from V and n). */
+int ts_set_sort_part(int32_t part);
+
+/* Tuning.  Work-groups per column block that finish cut rows in the combine launch (default 128). */
+int ts_set_combine_groups(int32_t groups);
 
 const char* ts_status_string(int status);
 

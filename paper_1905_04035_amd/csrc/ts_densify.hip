@@ -42,12 +42,17 @@ namespace {
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u2 __attribute__((ext_vector_type(2)));
 
-constexpr int kPart = 1024;        // ids owned by one sort work-group
+constexpr int kMaxPart = 1024;     // most ids one sort work-group owns (LDS: 16 x part x 4 B)
+constexpr int kMinPart = 128;
 constexpr int kSortWaves = 16;     // wavefronts per sort work-group
 constexpr int kColBlock = 256;     // fp32 columns per wavefront item (64 lanes x 4)
 constexpr int kMaxSlices = 64;
 constexpr int kSliceTokens = 16384;
-constexpr int kFusedSortMax = 32768;   // up to here one launch sorts everything
+constexpr int kFusedSortMax = 16384;   // up to here one launch sorts everything
+constexpr int kPieceSmallMax = 32768;  // up to here pieces of 16 positions, above 32
+constexpr int64_t kOverlapSortBytes = 112ll << 20;     // about what HBM moves while a sort launch runs
+constexpr int64_t kOverlapCombineBytes = 40ll << 20;   // same for the combine launch
+constexpr int kCombineGroups = 32;     // work-groups per column block in the combine kernel
 
 // ------------------------------------------------------------------ device helpers
 __device__ __forceinline__ uint64_t ballot64(bool p) { return __ballot(p); }
@@ -90,13 +95,13 @@ __device__ __forceinline__ f4 load_row4(uint64_t row_addr, int col);
 template <>
 __device__ __forceinline__ f4 load_row4<float>(uint64_t row_addr, int col)
 {
-    return *reinterpret_cast<const f4*>(row_addr + (uint64_t)col * 4u);
+    return __builtin_nontemporal_load(reinterpret_cast<const f4*>(row_addr + (uint64_t)col * 4u));
 }
 
 template <>
 __device__ __forceinline__ f4 load_row4<uint16_t>(uint64_t row_addr, int col)
 {
-    u2 b = *reinterpret_cast<const u2*>(row_addr + (uint64_t)col * 2u);
+    u2 b = __builtin_nontemporal_load(reinterpret_cast<const u2*>(row_addr + (uint64_t)col * 2u));
     f4 r;
     r.x = __uint_as_float(b.x << 16);
     r.y = __uint_as_float(b.x & 0xFFFF0000u);
@@ -108,6 +113,72 @@ __device__ __forceinline__ f4 load_row4<uint16_t>(uint64_t row_addr, int col)
 __device__ __forceinline__ f4 load_f4(const float* p) { return *reinterpret_cast<const f4*>(p); }
 __device__ __forceinline__ void store_f4(float* p, f4 v) { *reinterpret_cast<f4*>(p) = v; }
 
+// Streaming accesses for data that is touched once per call (value rows, dense_in,
+// dense_out): the nontemporal hint keeps them from displacing the sort's arrays and the
+// partial rows in the caches, and measures about 8 % faster on a plain [V, d] copy.
+__device__ __forceinline__ f4 load_f4_stream(const float* p)
+{
+    return __builtin_nontemporal_load(reinterpret_cast<const f4*>(p));
+}
+__device__ __forceinline__ void store_f4_stream(float* p, f4 v)
+{
+    __builtin_nontemporal_store(v, reinterpret_cast<f4*>(p));
+}
+
+// One wavefront copies dense row v (or writes zeros when there is no dense operand).
+__device__ __forceinline__ void copy_row(const float* dense_in, float* dense_out, int v, int d, int lane)
+{
+    const float* src = dense_in ? dense_in + (size_t)v * d : nullptr;
+    float* dst = dense_out + (size_t)v * d;
+    for (int c0 = 0; c0 < d; c0 += 4 * kColBlock) {
+        f4 x[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int col = c0 + u * kColBlock + lane * 4;
+            x[u] = (f4)(0.0f);
+            if (src && col < d) x[u] = load_f4_stream(src + col);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int col = c0 + u * kColBlock + lane * 4;
+            if (col < d) store_f4_stream(dst + col, x[u]);
+        }
+    }
+}
+
+// One wavefront copies dense rows v0 and v0 + 1 (those below vend; with CHECK only those
+// that received no pair): all loads of both rows are issued before the first store.
+template <bool CHECK>
+__device__ __forceinline__ void copy_two_rows(const float* dense_in, float* dense_out, const int32_t* count,
+                                              int v0, int vend, int d, int lane)
+{
+    bool go[2];
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        go[r] = v0 + r < vend;
+        if (CHECK && go[r]) go[r] = count[v0 + r] == 0;
+    }
+    if (!go[0] && !go[1]) return;
+    for (int c0 = 0; c0 < d; c0 += 4 * kColBlock) {
+        f4 x[2][4];
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int col = c0 + u * kColBlock + lane * 4;
+                x[r][u] = (f4)(0.0f);
+                if (go[r] && dense_in && col < d) x[r][u] = load_f4_stream(dense_in + (size_t)(v0 + r) * d + col);
+            }
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int col = c0 + u * kColBlock + lane * 4;
+                if (go[r] && col < d) store_f4_stream(dense_out + (size_t)(v0 + r) * d + col, x[r][u]);
+            }
+    }
+}
+
 // ------------------------------------------------------------------ shard table
 struct ShardTable {
     int32_t k;
@@ -116,85 +187,135 @@ struct ShardTable {
     const char* rows[TS_MAX_SHARDS];
 };
 
-// Calls f(shard, global index, valid, id) for 64 pairs at a time over [a, b), in
-// increasing index order, never mixing two shards in one call.  a and b are
-// wave-uniform.
-template <typename F>
-__device__ __forceinline__ void for_each_tile(const ShardTable& sh, int a, int b, int lane, F&& f)
+// Where pair idx lives: its id and the address of its value row.  Only shards j0..j1
+// (those that overlap the wavefront's range) are looked at; j0, j1 are wave-uniform.
+__device__ __forceinline__ void locate(const ShardTable& sh, int j0, int j1, int idx, bool valid,
+                                       int row_bytes, const int32_t*& idp, uint64_t& row_addr)
 {
-    if (a >= b) return;
-    int j = 0;
-    while (j < sh.k && sh.off[j + 1] <= a) ++j;
-    int t = a;
-    while (t < b && j < sh.k) {
-        const int hi = min(b, sh.off[j + 1]);
-        const int32_t* ids = sh.ids[j];
-        const int base = sh.off[j];
-        for (int tt = t; tt < hi; tt += 64) {
-            const int idx = tt + lane;
-            const bool valid = idx < hi;
-            const int32_t id = valid ? ids[idx - base] : -1;
-            f(j, idx, valid, id);
+    for (int j = j0; j <= j1; ++j) {
+        const int lo = sh.off[j], hi = sh.off[j + 1];
+        if (valid && idx >= lo && idx < hi) {
+            idp = sh.ids[j] + (idx - lo);
+            row_addr = (uint64_t)(uintptr_t)sh.rows[j] + (uint64_t)(idx - lo) * (uint64_t)row_bytes;
         }
-        t = max(t, hi);
-        ++j;
     }
 }
 
 // ------------------------------------------------------------------ sort
 struct SortParams {
     int32_t n, V, G, S, SL;
+    int32_t part;       // ids owned by one work-group (power of two)
     int32_t row_bytes;
     int32_t* count;
     int32_t* row_start;
     int32_t* perm;
     int32_t* srt_id;
     uint64_t* srt_addr;
-    uint32_t* tot;      // [S][G * kPart]  pairs per (slice, id)
+    uint32_t* tot;      // [S][G * part]   pairs per (slice, id)
     uint32_t* below;    // [S][G]          pairs of the slice with a valid id below the part
     uint32_t* bad;      // [S]             pairs of the slice with an id outside [0, V)
     int32_t* n_valid;
     int32_t* n_bad;
+    int32_t* n_cut;     // length of the list of cut rows, cleared here for the reduce kernel
+    // Work-groups past the sorting ones copy dense rows [copy_row0, copy_row1) to the output
+    // without knowing yet which rows receive pairs (the reduce kernel, which runs after,
+    // overwrites those).  It keeps HBM busy while the latency-bound sort runs.
+    const float* copy_in;
+    float* copy_out;
+    int32_t copy_row0, copy_row1, d;
+    int32_t stagger_wgs, stagger_sleeps;   // the first copy work-groups start a little later
 };
 
 enum { SORT_FUSED = 0, SORT_COUNT = 1, SORT_SCATTER = 2 };
 
+// One wavefront walks its sub-slice [a, b) in rounds of kRoundTiles tiles of 64 pairs.
+// All ids of a round are loaded before any is used, so a round costs one memory
+// latency; with a single round (every slice of at most 16384 pairs) the ids stay in
+// registers between the counting and the ranking pass.
+constexpr int kRoundTiles = 16;
+constexpr int kRoundPairs = kRoundTiles * 64;
+
+__device__ __forceinline__ void load_round(const ShardTable& sh, int j0, int j1, int a0, int b, int lane,
+                                           int32_t (&idr)[kRoundTiles])
+{
+#pragma unroll
+    for (int u = 0; u < kRoundTiles; ++u) {
+        // lanes past the end re-read the last pair, so that every load is unconditional
+        // and all of them are in flight together; such lanes are masked where ids are used
+        const int idx = min(a0 + u * 64 + lane, b - 1);
+        const int32_t* idp = sh.ids[j0];
+        uint64_t unused = 0;
+        locate(sh, j0, j1, idx, true, 0, idp, unused);
+        idr[u] = *idp;
+    }
+}
+
 template <int MODE>
 __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
 {
-    __shared__ uint32_t cnt[kSortWaves][kPart];
+    extern __shared__ uint32_t cnt[];          // [kSortWaves][part]
     __shared__ uint32_t red[3 * kSortWaves];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int g = blockIdx.x;
-    const int sl = blockIdx.y;
-    const int lo = g * kPart;
-    const uint32_t span = (uint32_t)min(kPart, p.V - lo);
+    const int nsort = p.G * p.S;
+    if ((int)blockIdx.x >= nsort) {
+        // Let the sort's own first loads (the ids) reach memory before the copy saturates it.
+        const int cw = (int)blockIdx.x - nsort;
+        if (cw < p.stagger_wgs)
+            for (int i = 0; i < p.stagger_sleeps; ++i) __builtin_amdgcn_s_sleep(32);
+        const int v = p.copy_row0 + (cw * kSortWaves + w) * 2;
+        copy_two_rows<false>(p.copy_in, p.copy_out, nullptr, v, p.copy_row1, p.d, lane);
+        return;
+    }
+    const int g = (int)blockIdx.x % p.G;
+    const int sl = (int)blockIdx.x / p.G;
+    const int part = p.part;
+    const int lo = g * part;
+    const uint32_t span = (uint32_t)min(part, p.V - lo);
+    uint32_t* const mycnt = cnt + w * part;
 
-    for (int i = tid; i < kSortWaves * kPart; i += 1024) (&cnt[0][0])[i] = 0u;
+    for (int i = tid; i < kSortWaves * part; i += 1024) cnt[i] = 0u;
 
     const int t0 = sl * p.SL;
     const int t1 = (int)min((int64_t)p.n, (int64_t)t0 + p.SL);
     const int L = p.SL / kSortWaves;
     const int a = (int)min((int64_t)t1, (int64_t)t0 + (int64_t)w * L);
     const int b = (int)min((int64_t)t1, (int64_t)a + L);
+    const int rounds = (b - a + kRoundPairs - 1) / kRoundPairs;
+    int j0 = 0;
+    while (j0 < sh.k - 1 && sh.off[j0 + 1] <= a) ++j0;
+    int j1 = j0;
+    while (j1 < sh.k - 1 && sh.off[j1 + 1] < b) ++j1;
+
+    int32_t idr[kRoundTiles];
+    if (rounds > 0) load_round(sh, j0, j1, a, b, lane, idr);
     __syncthreads();
 
     // pass 1: count owned pairs per (wavefront, id); count what lies below the part
     uint32_t below = 0, bad = 0;
-    for_each_tile(sh, a, b, lane, [&](int, int, bool valid, int32_t id) {
-        const uint32_t rel = (uint32_t)(id - lo);
-        if (valid && rel < span) atomicAdd(&cnt[w][rel], 1u);
-        below += (valid && id >= 0 && id < lo) ? 1u : 0u;
-        bad += (valid && (id < 0 || id >= p.V)) ? 1u : 0u;
-    });
+    for (int r = 0; r < rounds; ++r) {
+        const int a0 = a + r * kRoundPairs;
+        if (r > 0) load_round(sh, j0, j1, a0, b, lane, idr);
+#pragma unroll
+        for (int u = 0; u < kRoundTiles; ++u) {
+            const bool valid = a0 + u * 64 + lane < b;
+            const int32_t id = idr[u];
+            const uint32_t rel = (uint32_t)(id - lo);
+            if (valid && rel < span) atomicAdd(&mycnt[rel], 1u);
+            below += (valid && id >= 0 && id < lo) ? 1u : 0u;
+            bad += (valid && (id < 0 || id >= p.V)) ? 1u : 0u;
+        }
+    }
     __syncthreads();
 
+    const bool idt = tid < part;               // this thread speaks for id lo + tid
     uint32_t mine = 0;
+    if (idt) {
 #pragma unroll
-    for (int ww = 0; ww < kSortWaves; ++ww) mine += cnt[ww][tid];
+        for (int ww = 0; ww < kSortWaves; ++ww) mine += cnt[ww * part + tid];
+    }
     below = wave_sum(below);
     bad = wave_sum(bad);
     if (lane == 0) {
@@ -209,9 +330,9 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
         bad_wg += red[kSortWaves + ww];
     }
 
-    const size_t GV = (size_t)p.G * kPart;
+    const size_t GV = (size_t)p.G * part;
     if (MODE == SORT_COUNT) {
-        p.tot[(size_t)sl * GV + lo + tid] = mine;
+        if (idt) p.tot[(size_t)sl * GV + lo + tid] = mine;
         if (tid == 0) {
             p.below[sl * p.G + g] = below_wg;
             if (g == 0) p.bad[sl] = bad_wg;
@@ -225,7 +346,7 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
         base = 0;
         nbad = 0;
         for (int s2 = 0; s2 < p.S; ++s2) {
-            const uint32_t x = p.tot[(size_t)s2 * GV + lo + tid];
+            const uint32_t x = idt ? p.tot[(size_t)s2 * GV + lo + tid] : 0u;
             total += x;
             if (s2 < sl) pre += x;
             base += p.below[s2 * p.G + g];
@@ -250,50 +371,76 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
                 *p.n_valid = (int32_t)(rs + total);
             }
         }
-        if (g == 0 && tid == 0) *p.n_bad = (int32_t)nbad;
+        if (g == 0 && tid == 0) {
+            *p.n_bad = (int32_t)nbad;
+            *p.n_cut = 0;
+        }
     }
 
     // turn the per-wavefront counts into running positions
-    uint32_t o = rs + pre;
+    if (idt) {
+        uint32_t o = rs + pre;
 #pragma unroll
-    for (int ww = 0; ww < kSortWaves; ++ww) {
-        const uint32_t c = cnt[ww][tid];
-        cnt[ww][tid] = o;
-        o += c;
+        for (int ww = 0; ww < kSortWaves; ++ww) {
+            const uint32_t c = cnt[ww * part + tid];
+            cnt[ww * part + tid] = o;
+            o += c;
+        }
     }
     __syncthreads();
 
-    // pass 2: same walk; every owned pair takes the next position of its id.
-    // Pairs of one id inside a tile are ranked by lane, tiles are walked in order
-    // and wavefronts own consecutive sub-slices: the sort is stable.
-    volatile uint32_t* my = cnt[w];
-    for_each_tile(sh, a, b, lane, [&](int j, int idx, bool valid, int32_t id) {
-        const uint32_t rel = (uint32_t)(id - lo);
-        const bool own = valid && rel < span;
-        uint64_t m = ballot64(own);
-        uint32_t pos = 0;
-        while (m) {
-            const int l = __builtin_ctzll(m);
-            const uint32_t r = bcast(rel, l);
-            const bool same = own && rel == r;
-            const uint64_t sm = ballot64(same);
-            const uint32_t bse = my[r];
-            if (same) pos = bse + lanes_below(sm);
-            if (lane == l) my[r] = bse + (uint32_t)__popcll(sm);
-            m &= ~sm;
+    // pass 2: same walk; every owned pair takes the next position of its id.  Pairs of one
+    // id inside a tile are ranked by lane, tiles are walked in order and wavefronts own
+    // consecutive sub-slices, so the sort is stable.  Per tile: one LDS read of the running
+    // positions, a scalar loop over the distinct owned ids, one LDS write by the last lane
+    // of each id.
+    volatile uint32_t* my = mycnt;
+    for (int r = 0; r < rounds; ++r) {
+        const int a0 = a + r * kRoundPairs;
+        if (rounds > 1) load_round(sh, j0, j1, a0, b, lane, idr);
+#pragma unroll
+        for (int u = 0; u < kRoundTiles; ++u) {
+            if (a0 + u * 64 >= b) break;
+            const int idx = a0 + u * 64 + lane;
+            const bool valid = idx < b;
+            const int32_t id = idr[u];
+            const uint32_t rel = (uint32_t)(id - lo);
+            const bool own = valid && rel < span;
+            uint64_t m = ballot64(own);
+            if (m == 0) continue;
+            const uint32_t basev = own ? my[rel] : 0u;
+            uint32_t pos = 0, next = 0;
+            bool leader = false;
+            while (m) {
+                const int l = __builtin_ctzll(m);
+                const uint32_t rl = bcast(rel, l);
+                const bool same = own && rel == rl;
+                const uint64_t sm = ballot64(same);
+                if (same) pos = basev + lanes_below(sm);
+                if (lane == l) {
+                    leader = true;
+                    next = basev + (uint32_t)__popcll(sm);
+                }
+                m &= ~sm;
+            }
+            if (leader) my[rel] = next;
+            if (own) {
+                const int32_t* idp = nullptr;
+                uint64_t row_addr = 0;
+                locate(sh, j0, j1, idx, valid, p.row_bytes, idp, row_addr);
+                p.perm[pos] = idx;
+                p.srt_id[pos] = id;
+                p.srt_addr[pos] = row_addr;
+            }
         }
-        if (own) {
-            p.perm[pos] = idx;
-            p.srt_id[pos] = id;
-            p.srt_addr[pos] = (uint64_t)(uintptr_t)sh.rows[j] + (uint64_t)(idx - sh.off[j]) * (uint64_t)p.row_bytes;
-        }
-    });
+    }
 }
 
 // ------------------------------------------------------------------ reduce
 struct ReduceParams {
     int32_t V, d, C, ncb;
     int32_t n_piece_items;      // pieces x column blocks
+    int32_t copy_row0, copy_row1;   // copy items cover the untouched rows in this range
     const int32_t* count;
     const int32_t* row_start;
     const int32_t* srt_id;
@@ -302,6 +449,8 @@ struct ReduceParams {
     const float* dense_in;
     float* dense_out;
     float* partial;             // [2 * pieces][d]
+    int32_t* n_cut;             // number of cut rows found so far
+    int2* cut_list;             // (row id, first piece) of every cut row, in no particular order
 };
 
 template <typename RowT>
@@ -313,25 +462,10 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
 
     if (item >= p.n_piece_items) {
         // ---- copy item: one output row that received no pair
-        const int v = item - p.n_piece_items;
-        if (v >= p.V) return;
+        const int v = p.copy_row0 + item - p.n_piece_items;
+        if (v >= p.copy_row1) return;
         if (p.count[v] != 0) return;
-        const float* src = p.dense_in ? p.dense_in + (size_t)v * p.d : nullptr;
-        float* dst = p.dense_out + (size_t)v * p.d;
-        for (int c0 = 0; c0 < p.d; c0 += 4 * kColBlock) {
-            f4 x[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int col = c0 + u * kColBlock + lane * 4;
-                x[u] = (f4)(0.0f);
-                if (src && col < p.d) x[u] = load_f4(src + col);
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int col = c0 + u * kColBlock + lane * 4;
-                if (col < p.d) store_f4(dst + col, x[u]);
-            }
-        }
+        copy_row(p.dense_in, p.dense_out, v, p.d, lane);
         return;
     }
 
@@ -366,6 +500,11 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
     const uint64_t Lm = ballot64(last);
     const uint64_t W = ballot64(whole);
     if (A == 0) return;
+    // a cut row is announced once, by the item that holds its first pair
+    if (cb == 0 && active && !whole && wpos == s) {
+        const int e = atomicAdd(p.n_cut, 1);
+        p.cut_list[e] = make_int2(id, k);
+    }
     const int a = __builtin_ctzll(A);
     const int b = 64 - __builtin_clzll(A);
     const uint32_t slot = (uint32_t)(2 * k + (s >= pos0 ? 1 : 0));
@@ -384,7 +523,7 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
                 if (colok) r[u] = load_row4<RowT>(ra, col);
                 if (have_dense && (((Lm & W) >> j) & 1ull)) {
                     const int vj = (int)bcast((uint32_t)id, j);
-                    if (colok) dn[u] = load_f4(p.dense_in + (size_t)vj * p.d + col);
+                    if (colok) dn[u] = load_f4_stream(p.dense_in + (size_t)vj * p.d + col);
                 }
             }
         }
@@ -397,7 +536,7 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
                 if ((Lm >> j) & 1ull) {
                     if ((W >> j) & 1ull) {
                         const int vj = (int)bcast((uint32_t)id, j);
-                        if (colok) store_f4(p.dense_out + (size_t)vj * p.d + col, acc + dn[u]);
+                        if (colok) store_f4_stream(p.dense_out + (size_t)vj * p.d + col, acc + dn[u]);
                     } else {
                         const uint32_t sj = bcast(slot, j);
                         if (colok) store_f4(p.partial + (size_t)sj * p.d + col, acc);
@@ -413,48 +552,52 @@ struct CombineParams {
     int32_t V, d, C, ncb;
     const int32_t* count;
     const int32_t* row_start;
-    const int32_t* srt_id;
-    const int32_t* n_valid;
+    const int32_t* n_cut;
+    const int2* cut_list;
     const float* dense_in;
     float* dense_out;
     const float* partial;
+    int32_t groups;             // combining work-groups per column block
+    int32_t copy_row0, copy_row1;   // untouched rows copied by the work-groups past the combining ones
 };
 
+// Work-group (e, cb) finishes column block cb of the cut rows e, e + gridDim.x, ...
+// The P pieces of a row are split into 16 contiguous shares, one per wavefront, each
+// added in piece order; wavefront 0 then adds the shares in order and dense_in last.
 __global__ __launch_bounds__(1024) void combine_kernel(CombineParams p)
 {
     __shared__ f4 share[kSortWaves][64];
 
-    const int k = blockIdx.x;
-    const int C = p.C;
-    const int nvalid = *p.n_valid;
-    const int endpos = (k + 1) * C - 1;
-    if (endpos >= nvalid) return;
-    // the only output row that can start in piece k and be cut is the one that owns
-    // the piece's last position
-    const int v = p.srt_id[endpos];
-    const int c = p.count[v];
-    const int s = p.row_start[v];
-    if (c <= C || s < k * C) return;
-    const int P = (s + c - 1) / C - k + 1;      // pieces of this row, >= 2
-
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int cbw = min(p.ncb, kSortWaves);     // column blocks in flight
-    const int S = kSortWaves / cbw;             // shares per column block
-    const int cbi = w % cbw;
-    const int sh = w / cbw;
-    const int per = (P + S - 1) / S;
-    const int j0 = min(P, sh * per);
-    const int j1 = (sh < S) ? min(P, j0 + per) : j0;
+    const int ncombine = p.groups * p.ncb;
+    if ((int)blockIdx.x >= ncombine) {
+        const int v = p.copy_row0 + (((int)blockIdx.x - ncombine) * kSortWaves + w) * 2;
+        copy_two_rows<true>(p.dense_in, p.dense_out, p.count, v, p.copy_row1, p.d, lane);
+        return;
+    }
+    const int ncut = *p.n_cut;
+    const int cb = (int)blockIdx.x % p.ncb;
+    const int e0 = (int)blockIdx.x / p.ncb;
+    const int col = cb * kColBlock + lane * 4;
+    const bool colok = col < p.d;
+    const int C = p.C;
 
-    for (int cb = cbi; cb - cbi < p.ncb; cb += cbw) {
-        const int col = cb * kColBlock + lane * 4;
-        const bool colok = cb < p.ncb && col < p.d;
+    for (int e = e0; e < ncut; e += p.groups) {
+        const int2 ent = p.cut_list[e];
+        const int v = ent.x, k = ent.y;
+        const int c = p.count[v];
+        const int s = p.row_start[v];
+        const int P = (s + c - 1) / C - k + 1;      // pieces of this row, >= 2
+        const int per = (P + kSortWaves - 1) / kSortWaves;
+        const int j0 = min(P, w * per);
+        const int j1 = min(P, j0 + per);
+
         f4 acc = (f4)(0.0f);
-        for (int jb = j0; jb < j1; jb += 8) {
-            f4 x[8];
+        for (int jb = j0; jb < j1; jb += 16) {
+            f4 x[16];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < 16; ++u) {
                 const int j = jb + u;
                 x[u] = (f4)(0.0f);
                 if (j < j1 && colok) {
@@ -463,18 +606,18 @@ __global__ __launch_bounds__(1024) void combine_kernel(CombineParams p)
                 }
             }
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
+            for (int u = 0; u < 16; ++u)
                 if (jb + u < j1) acc += x[u];
         }
         share[w][lane] = acc;
         __syncthreads();
-        if (sh == 0 && colok) {
-            f4 tot = share[cbi][lane];
-            for (int q = 1; q < S; ++q)
-                if (q * per < P) tot += share[q * cbw + cbi][lane];
+        if (w == 0 && colok) {
+            f4 tot = share[0][lane];
+            for (int q = 1; q < kSortWaves; ++q)
+                if (q * per < P) tot += share[q][lane];
             f4 dn = (f4)(0.0f);
-            if (p.dense_in) dn = load_f4(p.dense_in + (size_t)v * p.d + col);
-            store_f4(p.dense_out + (size_t)v * p.d + col, tot + dn);
+            if (p.dense_in) dn = load_f4_stream(p.dense_in + (size_t)v * p.d + col);
+            store_f4_stream(p.dense_out + (size_t)v * p.d + col, tot + dn);
         }
         __syncthreads();
     }
@@ -509,16 +652,22 @@ __global__ __launch_bounds__(1024) void unique_kernel(const int32_t* count, int 
 
 // ------------------------------------------------------------------ host side
 struct Plan {
-    int32_t S, SL, G, C, NB, ncb;
-    size_t off_nvalid, off_nbad, off_count, off_row_start, off_perm, off_srt_id, off_srt_addr, off_tot,
+    int32_t S, SL, G, part, C, NB, ncb;
+    size_t off_nvalid, off_nbad, off_ncut, off_cut_list, off_count, off_row_start, off_perm, off_srt_id, off_srt_addr, off_tot,
         off_below, off_bad, off_partial, total;
 };
 
 int g_piece_override = 0;
+int64_t g_overlap_sort = -1;            // dense bytes (read + write) copied beside each sort launch; -1 = default
+int64_t g_overlap_combine = -1;         // same, beside the combine launch
+int32_t g_stagger_wgs = 256, g_stagger_sleeps = 0;
+int32_t g_part_override = 0;
+int32_t g_combine_groups = kCombineGroups;
 void* g_ws = nullptr;
 int64_t g_ws_bytes = 0;
 Plan g_last_plan;
 int32_t g_last_V = 0;
+int32_t g_last_info[8] = {0, 0, 0, 0, 0, 0, 0, 0};
 bool g_have_last = false;
 
 constexpr int kMaxProfile = 4096;
@@ -532,12 +681,11 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 int piece_tokens_for(int64_t n)
 {
     if (g_piece_override) return g_piece_override;
-    return n <= kFusedSortMax ? 16 : 32;
+    return n <= kPieceSmallMax ? 16 : 32;
 }
 
 void make_plan(int64_t n, int32_t d, int32_t V, Plan* pl)
 {
-    pl->G = (V + kPart - 1) / kPart;
     if (n <= kFusedSortMax) {
         pl->S = 1;
         pl->SL = (int32_t)align_up((size_t)(n > 0 ? n : 1), 1024);
@@ -551,13 +699,24 @@ void make_plan(int64_t n, int32_t d, int32_t V, Plan* pl)
         pl->S = (int32_t)S;
         pl->SL = (int32_t)SL;
     }
+    // ids per sort work-group: smaller parts shorten the sort (fewer owned pairs per tile),
+    // but every sorting work-group holds half of a compute unit and slows the copy that
+    // runs beside it; about 64 work-groups per slice measured best
+    int part = kMaxPart;
+    while (part > kMinPart && (int64_t)((V + part - 1) / part) < 64) part >>= 1;
+    if (g_part_override) part = g_part_override;
+    pl->part = part;
+    pl->G = (V + part - 1) / part;
     pl->C = piece_tokens_for(n);
     pl->NB = (int32_t)((n + pl->C - 1) / pl->C);
     pl->ncb = (d + kColBlock - 1) / kColBlock;
     size_t o = 0;
     pl->off_nvalid = o;
     pl->off_nbad = o + 4;
+    pl->off_ncut = o + 8;
     o = 256;
+    pl->off_cut_list = o;
+    o = align_up(o + (size_t)pl->NB * 8, 256);
     pl->off_count = o;
     o = align_up(o + (size_t)V * 4, 256);
     pl->off_row_start = o;
@@ -569,7 +728,7 @@ void make_plan(int64_t n, int32_t d, int32_t V, Plan* pl)
     pl->off_srt_addr = o;
     o = align_up(o + (size_t)n * 8, 256);
     pl->off_tot = o;
-    if (pl->S > 1) o = align_up(o + (size_t)pl->S * pl->G * kPart * 4, 256);
+    if (pl->S > 1) o = align_up(o + (size_t)pl->S * pl->G * pl->part * 4, 256);
     pl->off_below = o;
     if (pl->S > 1) o = align_up(o + (size_t)pl->S * pl->G * 4, 256);
     pl->off_bad = o;
@@ -597,6 +756,7 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     sp.G = pl.G;
     sp.S = pl.S;
     sp.SL = pl.SL;
+    sp.part = pl.part;
     sp.row_bytes = d * (row_dtype == TS_ROW_BF16 ? 2 : 4);
     sp.count = (int32_t*)(ws + pl.off_count);
     sp.row_start = (int32_t*)(ws + pl.off_row_start);
@@ -608,13 +768,40 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     sp.bad = (uint32_t*)(ws + pl.off_bad);
     sp.n_valid = (int32_t*)(ws + pl.off_nvalid);
     sp.n_bad = (int32_t*)(ws + pl.off_nbad);
+    sp.n_cut = (int32_t*)(ws + pl.off_ncut);
 
-    const dim3 sgrid((unsigned)pl.G, (unsigned)pl.S);
+    const bool in_place = dense_in == dense_out;
+    // rows copied by the sort launches: about as many bytes as HBM moves while a sort runs
+    const int64_t budget = g_overlap_sort >= 0 ? g_overlap_sort : kOverlapSortBytes;
+    int64_t rows_per_launch = in_place ? 0 : budget / ((int64_t)8 * d);
+    rows_per_launch = rows_per_launch / (2 * kSortWaves) * (2 * kSortWaves);
+    // rows copied by the combine launch, taken from the end
+    const int64_t budget_c = g_overlap_combine >= 0 ? g_overlap_combine : kOverlapCombineBytes;
+    int64_t rows_tail = (in_place || pl.NB == 0) ? 0 : budget_c / ((int64_t)8 * d);
+    rows_tail = rows_tail / (2 * kSortWaves) * (2 * kSortWaves);
+    if (rows_tail > V) rows_tail = V;
+    const int32_t tail0 = (int32_t)(V - rows_tail);
+    int32_t copy_done = 0;
+    auto sort_grid = [&](SortParams& q) {
+        q.copy_row0 = copy_done;
+        q.copy_row1 = (int32_t)(copy_done + rows_per_launch < tail0 ? copy_done + rows_per_launch : tail0);
+        copy_done = q.copy_row1;
+        return dim3((unsigned)(pl.G * pl.S + (q.copy_row1 - q.copy_row0 + 2 * kSortWaves - 1) / (2 * kSortWaves)));
+    };
+    sp.stagger_wgs = g_stagger_wgs;
+    sp.stagger_sleeps = g_stagger_sleeps;
+    sp.copy_in = dense_in;
+    sp.copy_out = dense_out;
+    sp.d = d;
+    const size_t lds = (size_t)kSortWaves * pl.part * sizeof(uint32_t);
     if (pl.S == 1) {
-        hipLaunchKernelGGL(sort_kernel<SORT_FUSED>, sgrid, dim3(1024), 0, stream, sp, sh);
+        const dim3 g1 = sort_grid(sp);
+        hipLaunchKernelGGL(sort_kernel<SORT_FUSED>, g1, dim3(1024), lds, stream, sp, sh);
     } else {
-        hipLaunchKernelGGL(sort_kernel<SORT_COUNT>, sgrid, dim3(1024), 0, stream, sp, sh);
-        hipLaunchKernelGGL(sort_kernel<SORT_SCATTER>, sgrid, dim3(1024), 0, stream, sp, sh);
+        const dim3 g1 = sort_grid(sp);
+        hipLaunchKernelGGL(sort_kernel<SORT_COUNT>, g1, dim3(1024), lds, stream, sp, sh);
+        const dim3 g2 = sort_grid(sp);
+        hipLaunchKernelGGL(sort_kernel<SORT_SCATTER>, g2, dim3(1024), lds, stream, sp, sh);
     }
     if (hipGetLastError() != hipSuccess) return TS_ERR_HIP;
 
@@ -632,8 +819,11 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     rp.dense_in = dense_in;
     rp.dense_out = dense_out;
     rp.partial = (float*)(ws + pl.off_partial);
-    const bool in_place = dense_in == dense_out;
-    const int64_t items = (int64_t)rp.n_piece_items + (in_place ? 0 : V);
+    rp.n_cut = sp.n_cut;
+    rp.cut_list = (int2*)(ws + pl.off_cut_list);
+    rp.copy_row0 = copy_done;
+    rp.copy_row1 = tail0;
+    const int64_t items = (int64_t)rp.n_piece_items + (in_place ? 0 : tail0 - copy_done);
     const unsigned rgrid = (unsigned)((items + 3) / 4);
 
     const bool prof = g_prof_used < g_prof_cap;
@@ -658,16 +848,28 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
         cp.ncb = pl.ncb;
         cp.count = sp.count;
         cp.row_start = sp.row_start;
-        cp.srt_id = sp.srt_id;
-        cp.n_valid = sp.n_valid;
+        cp.n_cut = sp.n_cut;
+        cp.cut_list = rp.cut_list;
         cp.dense_in = dense_in;
         cp.dense_out = dense_out;
         cp.partial = rp.partial;
-        hipLaunchKernelGGL(combine_kernel, dim3((unsigned)pl.NB), dim3(1024), 0, stream, cp);
+        cp.groups = pl.NB < g_combine_groups ? pl.NB : g_combine_groups;
+        cp.copy_row0 = tail0;
+        cp.copy_row1 = V;
+        const unsigned cgrid = (unsigned)(cp.groups * pl.ncb + (V - tail0 + 2 * kSortWaves - 1) / (2 * kSortWaves));
+        hipLaunchKernelGGL(combine_kernel, dim3(cgrid), dim3(1024), 0, stream, cp);
         if (hipGetLastError() != hipSuccess) return TS_ERR_HIP;
     }
     g_last_plan = pl;
     g_last_V = V;
+    g_last_info[0] = pl.C;
+    g_last_info[1] = copy_done;
+    g_last_info[2] = tail0;
+    g_last_info[3] = pl.S;
+    g_last_info[4] = pl.part;
+    g_last_info[5] = pl.NB;
+    g_last_info[6] = pl.NB > 0 ? (pl.NB < g_combine_groups ? pl.NB : g_combine_groups) : 0;
+    g_last_info[7] = in_place ? 1 : 0;
     g_have_last = true;
     return TS_OK;
 }
@@ -763,7 +965,7 @@ int ts_workspace_bytes(int64_t n_total, int32_t d, int32_t V, int64_t* bytes)
     if (n_total >= ((int64_t)1 << 31)) return TS_ERR_OVERFLOW;
     Plan a, b;
     make_plan(n_total, d, V, &a);
-    make_plan(n_total < kFusedSortMax ? n_total : kFusedSortMax, d, V, &b);
+    make_plan(n_total < kPieceSmallMax ? n_total : kPieceSmallMax, d, V, &b);
     *bytes = (int64_t)(a.total > b.total ? a.total : b.total);
     return TS_OK;
 }
@@ -794,6 +996,14 @@ int ts_last_views(const int32_t** count, const int32_t** row_start, const int32_
     if (perm) *perm = (const int32_t*)(ws + g_last_plan.off_perm);
     if (n_valid) *n_valid = (const int32_t*)(ws + g_last_plan.off_nvalid);
     if (n_bad_ids) *n_bad_ids = (const int32_t*)(ws + g_last_plan.off_nbad);
+    return TS_OK;
+}
+
+int ts_last_launch_info(int32_t* info)
+{
+    if (!info) return TS_ERR_NULL;
+    if (!g_have_last) return TS_ERR_WORKSPACE;
+    for (int i = 0; i < 8; ++i) info[i] = g_last_info[i];
     return TS_OK;
 }
 
@@ -831,6 +1041,36 @@ int ts_profile_end(float* ms_out, int32_t capacity, int32_t* n_out)
     *n_out = m;
     g_prof_cap = 0;
     g_prof_used = 0;
+    return TS_OK;
+}
+
+int ts_set_overlap_bytes(int64_t sort_bytes, int64_t combine_bytes)
+{
+    if (sort_bytes < -1 || combine_bytes < -1) return TS_ERR_SHAPE;
+    g_overlap_sort = sort_bytes;
+    g_overlap_combine = combine_bytes;
+    return TS_OK;
+}
+
+int ts_set_sort_part(int32_t part)
+{
+    if (part != 0 && part != 64 && part != 128 && part != 256 && part != 512 && part != 1024) return TS_ERR_SHAPE;
+    g_part_override = part;
+    return TS_OK;
+}
+
+int ts_set_combine_groups(int32_t groups)
+{
+    if (groups < 1 || groups > 65535) return TS_ERR_SHAPE;
+    g_combine_groups = groups;
+    return TS_OK;
+}
+
+int ts_set_stagger(int32_t work_groups, int32_t sleeps)
+{
+    if (work_groups < 0 || sleeps < 0 || sleeps > 64) return TS_ERR_SHAPE;
+    g_stagger_wgs = work_groups;
+    g_stagger_sleeps = sleeps;
     return TS_OK;
 }
 

@@ -105,6 +105,24 @@ def test_piece_sizes_and_exact_boundaries(piece):
         ts.ts_set_piece_tokens(0)
 
 
+@pytest.mark.parametrize("mib", [0, 1, 4096])
+def test_result_does_not_depend_on_the_overlapped_copy(mib):
+    w = wl.make_custom(V=5000, d=512, n_list=[6000, 3000], seed=46)
+    ref = run_gpu(w, mode="multi")
+    ts.ts_set_overlap_bytes(mib << 20, (mib // 2) << 20)
+    ts.ts_set_stagger(7, 2)
+    try:
+        _case(w, mode="multi")
+        got = run_gpu(w, mode="multi")
+        _case(w, mode="multi", dense=False)
+        wb = wl.make_custom(V=3000, d=256, n_list=[40000], seed=47)      # two sort launches
+        _case(wb)
+    finally:
+        ts.ts_set_overlap_bytes(-1, -1)
+        ts.ts_set_stagger(256, 0)
+    assert np.array_equal(ref["out"].view(np.uint32), got["out"].view(np.uint32))
+
+
 def test_no_dense_operand_and_in_place():
     w = wl.make_custom(V=3000, d=256, n_list=[5000, 1000], seed=41)
     _case(w, dense=False)                     # Listing 1 alone: untouched rows are +0.0
