@@ -44,6 +44,9 @@ def main():
     ap.add_argument("--overlap-combine-mib", type=float, default=-1.0, help="tuning; -1 = library default")
     ap.add_argument("--stagger", type=int, nargs=2, default=None, metavar=("WGS", "SLEEPS"), help="tuning")
     ap.add_argument("--piece-tokens", type=int, default=0, help="tuning; 0 = library default")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run the same launches with n = 0: a plain [V, d] copy of known size, used to "
+                         "scale hardware byte counters")
     ap.add_argument("--no-events", action="store_true",
                     help="do not record per-kernel HIP events inside the timed region")
     args = ap.parse_args()
@@ -93,6 +96,23 @@ def main():
         sets.append(s)
     ws = ts.Workspace(n, d, V, dev)
     stream = torch.cuda.current_stream()
+
+    if args.calibrate_copy:
+        empty_ids = torch.empty(0, dtype=torch.int32, device=dev)
+        empty_rows = torch.empty((0, d), dtype=torch.float32, device=dev)
+        for i in range(args.warmup + args.steps):
+            s = sets[i % len(sets)]
+            ts.ts_densify(empty_ids, empty_rows, d, V, s["dense_in"], s["dense_out"], stream)
+        torch.cuda.synchronize()
+        info = ts.ts_last_launch_info()
+        x = info["sort_copy_rows_end"]
+        print(json.dumps({"calibration": "ts_densify with n = 0 copies dense_in to dense_out",
+                          "launches_per_step": {"sort_kernel": {"read_bytes": 4 * d * x, "write_bytes": 4 * d * x},
+                                                "reduce_kernel": {"read_bytes": 4 * d * (V - x),
+                                                                  "write_bytes": 4 * d * (V - x)}},
+                          "steps": args.warmup + args.steps}))
+        ws.close()
+        return
 
     def step(i):
         s = sets[i % len(sets)]

@@ -1,0 +1,121 @@
+"""No GPU needed: the C-ABI library loads, exports every symbol the header declares, and its
+host-side checks and byte arithmetic behave as documented.  No kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_1905_04035_amd import binding as ts
+from paper_1905_04035_amd import build as hip_build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "ts_densify.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    hip_build.build(force=False)
+    return ts.lib()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ts_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert {"ts_densify", "ts_densify_bf16", "ts_densify_multi", "ts_buffer_bytes"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), f"{name} is declared in the header but not exported"
+
+
+def test_the_binding_offers_the_same_names():
+    for name in declared_functions():
+        if name in ("ts_status_string",):
+            continue
+        assert hasattr(ts, name) or hasattr(ts, name + "_raw"), name
+
+
+def test_buffer_bytes_formulas_and_errors(lib):
+    assert ts.ts_buffer_bytes(16, 16384, 1024, 32768) == (16 * 16384 * (4 + 4 * 1024), 4 * 32768 * 1024)
+    assert ts.ts_buffer_bytes(16, 16384, 1024, 32768) == (1074790400, 134217728)
+    assert ts.ts_buffer_bytes(2, 65536, 1024, 32768, ts.TS_ROW_BF16)[0] == 2 * 65536 * (4 + 2 * 1024)
+    g1, d1 = ts.ts_buffer_bytes(1, 1000, 64, 1000)
+    g64, d64 = ts.ts_buffer_bytes(64, 1000, 64, 1000)
+    assert g64 == 64 * g1 and d64 == d1              # a gather grows with the workers, a reduce does not
+    assert ts.ts_buffer_bytes(0, 0, 4, 1) == (0, 16)
+    g, d = C.c_int64(0), C.c_int64(0)
+    assert lib.ts_buffer_bytes(1, 1, 0, 1, 0, C.byref(g), C.byref(d)) == ts.TS_ERR_SHAPE
+    assert lib.ts_buffer_bytes(1, 1, 4, 1, 7, C.byref(g), C.byref(d)) == ts.TS_ERR_SHAPE
+    assert lib.ts_buffer_bytes(-1, 1, 4, 1, 0, C.byref(g), C.byref(d)) == ts.TS_ERR_SHAPE
+    assert lib.ts_buffer_bytes(1, 1, 4, 1, 0, None, C.byref(d)) == ts.TS_ERR_NULL
+    assert lib.ts_buffer_bytes(2 ** 40, 2 ** 40, 1024, 1, 0, C.byref(g), C.byref(d)) == ts.TS_ERR_OVERFLOW
+
+
+def test_workspace_bytes(lib):
+    small = ts.ts_workspace_bytes(16384, 1024, 32768)
+    big = ts.ts_workspace_bytes(262144, 1024, 32768)
+    assert 0 < small < big < 2 ** 30
+    assert ts.ts_workspace_bytes(0, 4, 1) > 0
+    prev = 0
+    for n in (1, 100, 16384, 16385, 32768, 32769, 100000, 1000000):
+        b = ts.ts_workspace_bytes(n, 256, 5000)
+        assert b >= prev
+        prev = b
+    out = C.c_int64(0)
+    assert lib.ts_workspace_bytes(10, 6, 10, C.byref(out)) == ts.TS_ERR_SHAPE        # d % 4 != 0
+    assert lib.ts_workspace_bytes(-1, 4, 10, C.byref(out)) == ts.TS_ERR_SHAPE
+    assert lib.ts_workspace_bytes(2 ** 31, 4, 10, C.byref(out)) == ts.TS_ERR_OVERFLOW
+    assert lib.ts_workspace_bytes(10, 4, 10, None) == ts.TS_ERR_NULL
+
+
+def test_argument_checks_happen_before_any_launch(lib):
+    ts.ts_bind_workspace(None)
+    fake = 0x1000      # 16-byte aligned, never dereferenced: every call below fails a host check first
+    f = lambda *a: lib.ts_densify(*a)
+    assert f(fake, fake, 4, 8, 16, None, None, None) == ts.TS_ERR_NULL
+    assert f(None, fake, 4, 8, 16, None, fake, None) == ts.TS_ERR_NULL
+    assert f(fake, None, 4, 8, 16, None, fake, None) == ts.TS_ERR_NULL
+    assert f(fake, fake, -1, 8, 16, None, fake, None) == ts.TS_ERR_SHAPE
+    assert f(fake, fake, 4, 6, 16, None, fake, None) == ts.TS_ERR_SHAPE
+    assert f(fake, fake, 4, 8, 0, None, fake, None) == ts.TS_ERR_SHAPE
+    assert f(fake, fake, 2 ** 31, 8, 16, None, fake, None) == ts.TS_ERR_OVERFLOW
+    assert f(fake, fake + 4, 4, 8, 16, None, fake, None) == ts.TS_ERR_ALIGN
+    assert f(fake, fake, 4, 8, 16, fake + 8, fake, None) == ts.TS_ERR_ALIGN
+    assert f(fake, fake, 4, 8, 16, None, fake, None) == ts.TS_ERR_WORKSPACE      # nothing bound
+    ids = (C.c_void_p * 1)(fake)
+    n = (C.c_int64 * 1)(4)
+    assert lib.ts_densify_multi(ids, ids, n, 0, 0, 8, 16, None, fake, None) == ts.TS_ERR_SHAPE
+    assert lib.ts_densify_multi(ids, ids, n, ts.TS_MAX_SHARDS + 1, 0, 8, 16, None, fake, None) == ts.TS_ERR_SHAPE
+    assert lib.ts_densify_multi(ids, ids, n, 1, 9, 8, 16, None, fake, None) == ts.TS_ERR_SHAPE
+    assert lib.ts_densify_multi(None, ids, n, 1, 0, 8, 16, None, fake, None) == ts.TS_ERR_NULL
+    assert lib.ts_bind_workspace(C.c_void_p(fake + 8), 1 << 20) == ts.TS_ERR_ALIGN
+    assert lib.ts_last_views(None, None, None, None, None) == ts.TS_ERR_WORKSPACE
+
+
+def test_tuning_setters_validate(lib):
+    assert lib.ts_set_piece_tokens(7) == ts.TS_ERR_SHAPE
+    assert lib.ts_set_piece_tokens(0) == ts.TS_OK
+    assert lib.ts_set_sort_part(100) == ts.TS_ERR_SHAPE
+    assert lib.ts_set_sort_part(0) == ts.TS_OK
+    assert lib.ts_set_overlap_bytes(-2, 0) == ts.TS_ERR_SHAPE
+    assert lib.ts_set_overlap_bytes(-1, -1) == ts.TS_OK
+    assert lib.ts_set_combine_groups(0) == ts.TS_ERR_SHAPE
+    assert lib.ts_set_combine_groups(32) == ts.TS_OK
+    assert lib.ts_set_stagger(256, 0) == ts.TS_OK
+
+
+def test_status_strings(lib):
+    seen = {ts.status_string(i) for i in range(7)}
+    assert len(seen) == 7 and "ok" in seen
+    assert "unknown" in ts.status_string(99)
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(ts, "_lib", None)
+    monkeypatch.setattr(ts, "LIB_PATH", "/nonexistent/libts_densify.so")
+    with pytest.raises(FileNotFoundError):
+        ts.lib()
