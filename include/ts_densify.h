@@ -107,11 +107,14 @@ int ts_bind_workspace(void* ws, int64_t bytes);
 /*
  * Views into the bound workspace describing the most recent densify call, valid
  * (in stream order) until the next one: count int32 [V] pairs per row,
- * row_start int32 [V + 1] exclusive prefix of count, perm int32 [n_valid] input
- * positions sorted by (id, position), n_valid and n_bad_ids int32 scalars.  Any
- * out-pointer may be NULL.  All returned pointers are device pointers.
+ * row_start int32 [V + 1] exclusive prefix of count, sorted [n_valid] records of
+ * TS_SORTED_PAIR_BYTES bytes each, in (id, input position) order, whose int32 words
+ * 2 and 3 are the pair's id and its position in the input, n_valid and n_bad_ids
+ * int32 scalars.  Any out-pointer may be NULL.  All returned pointers are device
+ * pointers.
  */
-int ts_last_views(const int32_t** count, const int32_t** row_start, const int32_t** perm,
+#define TS_SORTED_PAIR_BYTES 32
+int ts_last_views(const int32_t** count, const int32_t** row_start, const void** sorted,
                   const int32_t** n_valid, const int32_t** n_bad_ids);
 
 /*

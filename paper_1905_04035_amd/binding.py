@@ -173,7 +173,7 @@ class Workspace:
 
 def ts_last_views(V: int, n: int):
     """(count[V], row_start[V+1], perm[n_valid], n_valid, n_bad_ids) of the last call, copied to
-    the host after a synchronise."""
+    the host after a synchronise; perm is the input position of every sorted pair."""
     ptrs = [C.c_void_p() for _ in range(5)]
     _check(lib().ts_last_views(*[C.byref(p) for p in ptrs]), "ts_last_views")
     torch.cuda.synchronize()
@@ -189,7 +189,8 @@ def ts_last_views(V: int, n: int):
 
     n_valid = int(fetch(ptrs[3], 1)[0])
     n_bad = int(fetch(ptrs[4], 1)[0])
-    return fetch(ptrs[0], V), fetch(ptrs[1], V + 1), fetch(ptrs[2], min(n_valid, n)), n_valid, n_bad
+    records = fetch(ptrs[2], 8 * min(n_valid, n)).view(-1, 8)      # TS_SORTED_PAIR_BYTES = 32
+    return fetch(ptrs[0], V), fetch(ptrs[1], V + 1), records[:, 3].contiguous(), n_valid, n_bad
 
 
 _hiprt = None

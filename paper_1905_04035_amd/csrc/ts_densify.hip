@@ -41,9 +41,26 @@ namespace {
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+
+// One sorted pair, as the sort leaves it for the reduce kernel: where its value row is, and
+// everything the reduce kernel needs to know about the output row it belongs to.
+struct alignas(32) SortedPair {
+    uint64_t row_addr;
+    int32_t id;
+    int32_t pos;        // position of the pair in the input (concatenation order)
+    int32_t count;      // pairs of this id
+    int32_t row_start;  // sorted position of the id's first pair
+    int32_t pad[2];
+};
+static_assert(sizeof(SortedPair) == 32, "two 16-byte accesses per record");
 
 constexpr int kMaxPart = 1024;     // most ids one sort work-group owns (LDS: 16 x part x 4 B)
 constexpr int kMinPart = 128;
+#ifndef TS_BIG_COPY_ROWS
+#define TS_BIG_COPY_ROWS 1
+#endif
+constexpr int kBigCopyRows = TS_BIG_COPY_ROWS;   // rows per wavefront in the copying work-groups of 1024 threads
 constexpr int kSortWaves = 16;     // wavefronts per sort work-group
 constexpr int kColBlock = 256;     // fp32 columns per wavefront item (64 lanes x 4)
 constexpr int kMaxSlices = 64;
@@ -125,44 +142,25 @@ __device__ __forceinline__ void store_f4_stream(float* p, f4 v)
     __builtin_nontemporal_store(v, reinterpret_cast<f4*>(p));
 }
 
-// One wavefront copies dense row v (or writes zeros when there is no dense operand).
-__device__ __forceinline__ void copy_row(const float* dense_in, float* dense_out, int v, int d, int lane)
+// One wavefront copies the dense rows v0 .. v0 + R - 1 that lie below vend (with CHECK only
+// those that received no pair): all loads of all rows are issued before the first store.
+template <bool CHECK, int R>
+__device__ __forceinline__ void copy_rows(const float* dense_in, float* dense_out, const int32_t* count,
+                                          int v0, int vend, int d, int lane)
 {
-    const float* src = dense_in ? dense_in + (size_t)v * d : nullptr;
-    float* dst = dense_out + (size_t)v * d;
-    for (int c0 = 0; c0 < d; c0 += 4 * kColBlock) {
-        f4 x[4];
+    bool go[R];
+    bool any = false;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int col = c0 + u * kColBlock + lane * 4;
-            x[u] = (f4)(0.0f);
-            if (src && col < d) x[u] = load_f4_stream(src + col);
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int col = c0 + u * kColBlock + lane * 4;
-            if (col < d) store_f4_stream(dst + col, x[u]);
-        }
-    }
-}
-
-// One wavefront copies dense rows v0 and v0 + 1 (those below vend; with CHECK only those
-// that received no pair): all loads of both rows are issued before the first store.
-template <bool CHECK>
-__device__ __forceinline__ void copy_two_rows(const float* dense_in, float* dense_out, const int32_t* count,
-                                              int v0, int vend, int d, int lane)
-{
-    bool go[2];
-#pragma unroll
-    for (int r = 0; r < 2; ++r) {
+    for (int r = 0; r < R; ++r) {
         go[r] = v0 + r < vend;
         if (CHECK && go[r]) go[r] = count[v0 + r] == 0;
+        any = any || go[r];
     }
-    if (!go[0] && !go[1]) return;
+    if (!any) return;
     for (int c0 = 0; c0 < d; c0 += 4 * kColBlock) {
-        f4 x[2][4];
+        f4 x[R][4];
 #pragma unroll
-        for (int r = 0; r < 2; ++r)
+        for (int r = 0; r < R; ++r)
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int col = c0 + u * kColBlock + lane * 4;
@@ -170,7 +168,7 @@ __device__ __forceinline__ void copy_two_rows(const float* dense_in, float* dens
                 if (go[r] && dense_in && col < d) x[r][u] = load_f4_stream(dense_in + (size_t)(v0 + r) * d + col);
             }
 #pragma unroll
-        for (int r = 0; r < 2; ++r)
+        for (int r = 0; r < R; ++r)
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int col = c0 + u * kColBlock + lane * 4;
@@ -208,9 +206,7 @@ struct SortParams {
     int32_t row_bytes;
     int32_t* count;
     int32_t* row_start;
-    int32_t* perm;
-    int32_t* srt_id;
-    uint64_t* srt_addr;
+    SortedPair* sorted;
     uint32_t* tot;      // [S][G * part]   pairs per (slice, id)
     uint32_t* below;    // [S][G]          pairs of the slice with a valid id below the part
     uint32_t* bad;      // [S]             pairs of the slice with an id outside [0, V)
@@ -253,7 +249,7 @@ __device__ __forceinline__ void load_round(const ShardTable& sh, int j0, int j1,
 template <int MODE>
 __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
 {
-    extern __shared__ uint32_t cnt[];          // [kSortWaves][part]
+    extern __shared__ uint32_t cnt[];          // [kSortWaves][part] counts, then [2][part] per-id totals and starts
     __shared__ uint32_t red[3 * kSortWaves];
 
     const int tid = threadIdx.x;
@@ -265,8 +261,8 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
         const int cw = (int)blockIdx.x - nsort;
         if (cw < p.stagger_wgs)
             for (int i = 0; i < p.stagger_sleeps; ++i) __builtin_amdgcn_s_sleep(32);
-        const int v = p.copy_row0 + (cw * kSortWaves + w) * 2;
-        copy_two_rows<false>(p.copy_in, p.copy_out, nullptr, v, p.copy_row1, p.d, lane);
+        const int v = p.copy_row0 + (cw * kSortWaves + w) * kBigCopyRows;
+        copy_rows<false, kBigCopyRows>(p.copy_in, p.copy_out, nullptr, v, p.copy_row1, p.d, lane);
         return;
     }
     const int g = (int)blockIdx.x % p.G;
@@ -377,8 +373,13 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
         }
     }
 
-    // turn the per-wavefront counts into running positions
+    // turn the per-wavefront counts into running positions; keep each id's count and first
+    // position where the ranking pass can read them
+    uint32_t* const id_total = cnt + kSortWaves * part;
+    uint32_t* const id_start = id_total + part;
     if (idt) {
+        id_total[tid] = total;
+        id_start[tid] = rs;
         uint32_t o = rs + pre;
 #pragma unroll
         for (int ww = 0; ww < kSortWaves; ++ww) {
@@ -409,6 +410,8 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
             uint64_t m = ballot64(own);
             if (m == 0) continue;
             const uint32_t basev = own ? my[rel] : 0u;
+            const uint32_t tot_l = own ? id_total[rel] : 0u;
+            const uint32_t rs_l = own ? id_start[rel] : 0u;
             uint32_t pos = 0, next = 0;
             bool leader = false;
             while (m) {
@@ -428,9 +431,18 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
                 const int32_t* idp = nullptr;
                 uint64_t row_addr = 0;
                 locate(sh, j0, j1, idx, valid, p.row_bytes, idp, row_addr);
-                p.perm[pos] = idx;
-                p.srt_id[pos] = id;
-                p.srt_addr[pos] = row_addr;
+                u4* rec = reinterpret_cast<u4*>(p.sorted + pos);
+                u4 r0, r1;
+                r0.x = (uint32_t)row_addr;
+                r0.y = (uint32_t)(row_addr >> 32);
+                r0.z = (uint32_t)id;
+                r0.w = (uint32_t)idx;
+                r1.x = tot_l;
+                r1.y = rs_l;
+                r1.z = 0u;
+                r1.w = 0u;
+                rec[0] = r0;
+                rec[1] = r1;
             }
         }
     }
@@ -442,15 +454,14 @@ struct ReduceParams {
     int32_t n_piece_items;      // pieces x column blocks
     int32_t copy_row0, copy_row1;   // copy items cover the untouched rows in this range
     const int32_t* count;
-    const int32_t* row_start;
-    const int32_t* srt_id;
-    const uint64_t* srt_addr;
+    const SortedPair* sorted;
+    int32_t n;                  // pairs in the call (records beyond n_valid hold nothing)
     const int32_t* n_valid;
     const float* dense_in;
     float* dense_out;
     float* partial;             // [2 * pieces][d]
     int32_t* n_cut;             // number of cut rows found so far
-    int2* cut_list;             // (row id, first piece) of every cut row, in no particular order
+    int4* cut_list;             // (row id, first piece, pieces, -) of every cut row, in no particular order
 };
 
 template <typename RowT>
@@ -461,11 +472,9 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
     const int item = blockIdx.x * 4 + wave;
 
     if (item >= p.n_piece_items) {
-        // ---- copy item: one output row that received no pair
+        // ---- copy item: one output row, copied if it received no pair
         const int v = p.copy_row0 + item - p.n_piece_items;
-        if (v >= p.copy_row1) return;
-        if (p.count[v] != 0) return;
-        copy_row(p.dense_in, p.dense_out, v, p.d, lane);
+        copy_rows<true, 1>(p.dense_in, p.dense_out, p.count, v, p.copy_row1, p.d, lane);
         return;
     }
 
@@ -476,21 +485,26 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
     const bool colok = col < p.d;
     const int C = p.C;
     const int pos0 = k * C;
-    const int nvalid = *p.n_valid;
-    if (pos0 >= nvalid) return;
 
     // lane j looks at sorted position pos0 + j; the window is two pieces long because
     // an output row with at most C pairs that starts in this piece is finished here.
+    // The records are read before n_valid is known (one memory latency instead of two);
+    // what lies at or beyond n_valid is ignored.
     const int wpos = pos0 + lane;
-    const bool inwin = lane < 2 * C && wpos < nvalid;
-    int32_t id = -1, c = 0, s = 0;
-    uint64_t addr = 0;
-    if (inwin) {
-        id = p.srt_id[wpos];
-        addr = p.srt_addr[wpos];
-        c = p.count[id];
-        s = p.row_start[id];
+    const bool inarr = lane < 2 * C && wpos < p.n;
+    u4 r0 = (u4)(0u), r1 = (u4)(0u);
+    if (inarr) {
+        const u4* rec = reinterpret_cast<const u4*>(p.sorted + wpos);
+        r0 = rec[0];
+        r1 = rec[1];
     }
+    const int nvalid = *p.n_valid;
+    if (pos0 >= nvalid) return;
+    const bool inwin = inarr && wpos < nvalid;
+    const int32_t id = inwin ? (int32_t)r0.z : -1;
+    const int32_t c = inwin ? (int32_t)r1.x : 0;
+    const int32_t s = inwin ? (int32_t)r1.y : 0;
+    const uint64_t addr = inwin ? (((uint64_t)r0.y << 32) | r0.x) : 0ull;
     const bool whole = c <= C;       // output row small enough to be summed by one item
     const bool active = inwin && (whole ? (s >= pos0 && s < pos0 + C) : (lane < C));
     const bool first = active && (wpos == s || (!whole && lane == 0));
@@ -503,7 +517,7 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
     // a cut row is announced once, by the item that holds its first pair
     if (cb == 0 && active && !whole && wpos == s) {
         const int e = atomicAdd(p.n_cut, 1);
-        p.cut_list[e] = make_int2(id, k);
+        p.cut_list[e] = make_int4(id, k, (s + c - 1) / C - k + 1, 0);
     }
     const int a = __builtin_ctzll(A);
     const int b = 64 - __builtin_clzll(A);
@@ -551,9 +565,8 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
 struct CombineParams {
     int32_t V, d, C, ncb;
     const int32_t* count;
-    const int32_t* row_start;
     const int32_t* n_cut;
-    const int2* cut_list;
+    const int4* cut_list;
     const float* dense_in;
     float* dense_out;
     const float* partial;
@@ -572,23 +585,23 @@ __global__ __launch_bounds__(1024) void combine_kernel(CombineParams p)
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int ncombine = p.groups * p.ncb;
     if ((int)blockIdx.x >= ncombine) {
-        const int v = p.copy_row0 + (((int)blockIdx.x - ncombine) * kSortWaves + w) * 2;
-        copy_two_rows<true>(p.dense_in, p.dense_out, p.count, v, p.copy_row1, p.d, lane);
+        const int v = p.copy_row0 + (((int)blockIdx.x - ncombine) * kSortWaves + w) * kBigCopyRows;
+        copy_rows<true, kBigCopyRows>(p.dense_in, p.dense_out, p.count, v, p.copy_row1, p.d, lane);
         return;
     }
-    const int ncut = *p.n_cut;
     const int cb = (int)blockIdx.x % p.ncb;
     const int e0 = (int)blockIdx.x / p.ncb;
+    int4 ent = p.cut_list[e0];          // read beside n_cut; meaningless when e0 >= n_cut
+    const int ncut = *p.n_cut;
     const int col = cb * kColBlock + lane * 4;
     const bool colok = col < p.d;
-    const int C = p.C;
 
     for (int e = e0; e < ncut; e += p.groups) {
-        const int2 ent = p.cut_list[e];
+        if (e != e0) ent = p.cut_list[e];
         const int v = ent.x, k = ent.y;
-        const int c = p.count[v];
-        const int s = p.row_start[v];
-        const int P = (s + c - 1) / C - k + 1;      // pieces of this row, >= 2
+        const int P = ent.z;                        // pieces of this row, >= 2
+        f4 dn = (f4)(0.0f);
+        if (w == 0 && colok && p.dense_in) dn = load_f4_stream(p.dense_in + (size_t)v * p.d + col);
         const int per = (P + kSortWaves - 1) / kSortWaves;
         const int j0 = min(P, w * per);
         const int j1 = min(P, j0 + per);
@@ -615,8 +628,6 @@ __global__ __launch_bounds__(1024) void combine_kernel(CombineParams p)
             f4 tot = share[0][lane];
             for (int q = 1; q < kSortWaves; ++q)
                 if (q * per < P) tot += share[q][lane];
-            f4 dn = (f4)(0.0f);
-            if (p.dense_in) dn = load_f4_stream(p.dense_in + (size_t)v * p.d + col);
             store_f4_stream(p.dense_out + (size_t)v * p.d + col, tot + dn);
         }
         __syncthreads();
@@ -653,7 +664,7 @@ __global__ __launch_bounds__(1024) void unique_kernel(const int32_t* count, int 
 // ------------------------------------------------------------------ host side
 struct Plan {
     int32_t S, SL, G, part, C, NB, ncb;
-    size_t off_nvalid, off_nbad, off_ncut, off_cut_list, off_count, off_row_start, off_perm, off_srt_id, off_srt_addr, off_tot,
+    size_t off_nvalid, off_nbad, off_ncut, off_cut_list, off_count, off_row_start, off_sorted, off_tot,
         off_below, off_bad, off_partial, total;
 };
 
@@ -716,17 +727,13 @@ void make_plan(int64_t n, int32_t d, int32_t V, Plan* pl)
     pl->off_ncut = o + 8;
     o = 256;
     pl->off_cut_list = o;
-    o = align_up(o + (size_t)pl->NB * 8, 256);
+    o = align_up(o + (size_t)pl->NB * 16, 256);
     pl->off_count = o;
     o = align_up(o + (size_t)V * 4, 256);
     pl->off_row_start = o;
     o = align_up(o + ((size_t)V + 1) * 4, 256);
-    pl->off_perm = o;
-    o = align_up(o + (size_t)n * 4, 256);
-    pl->off_srt_id = o;
-    o = align_up(o + (size_t)n * 4, 256);
-    pl->off_srt_addr = o;
-    o = align_up(o + (size_t)n * 8, 256);
+    pl->off_sorted = o;
+    o = align_up(o + (size_t)n * sizeof(SortedPair), 256);
     pl->off_tot = o;
     if (pl->S > 1) o = align_up(o + (size_t)pl->S * pl->G * pl->part * 4, 256);
     pl->off_below = o;
@@ -760,9 +767,7 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     sp.row_bytes = d * (row_dtype == TS_ROW_BF16 ? 2 : 4);
     sp.count = (int32_t*)(ws + pl.off_count);
     sp.row_start = (int32_t*)(ws + pl.off_row_start);
-    sp.perm = (int32_t*)(ws + pl.off_perm);
-    sp.srt_id = (int32_t*)(ws + pl.off_srt_id);
-    sp.srt_addr = (uint64_t*)(ws + pl.off_srt_addr);
+    sp.sorted = (SortedPair*)(ws + pl.off_sorted);
     sp.tot = (uint32_t*)(ws + pl.off_tot);
     sp.below = (uint32_t*)(ws + pl.off_below);
     sp.bad = (uint32_t*)(ws + pl.off_bad);
@@ -774,11 +779,11 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     // rows copied by the sort launches: about as many bytes as HBM moves while a sort runs
     const int64_t budget = g_overlap_sort >= 0 ? g_overlap_sort : kOverlapSortBytes;
     int64_t rows_per_launch = in_place ? 0 : budget / ((int64_t)8 * d);
-    rows_per_launch = rows_per_launch / (2 * kSortWaves) * (2 * kSortWaves);
+    rows_per_launch = rows_per_launch / (kBigCopyRows * kSortWaves) * (kBigCopyRows * kSortWaves);
     // rows copied by the combine launch, taken from the end
     const int64_t budget_c = g_overlap_combine >= 0 ? g_overlap_combine : kOverlapCombineBytes;
     int64_t rows_tail = (in_place || pl.NB == 0) ? 0 : budget_c / ((int64_t)8 * d);
-    rows_tail = rows_tail / (2 * kSortWaves) * (2 * kSortWaves);
+    rows_tail = rows_tail / (kBigCopyRows * kSortWaves) * (kBigCopyRows * kSortWaves);
     if (rows_tail > V) rows_tail = V;
     const int32_t tail0 = (int32_t)(V - rows_tail);
     int32_t copy_done = 0;
@@ -786,14 +791,14 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
         q.copy_row0 = copy_done;
         q.copy_row1 = (int32_t)(copy_done + rows_per_launch < tail0 ? copy_done + rows_per_launch : tail0);
         copy_done = q.copy_row1;
-        return dim3((unsigned)(pl.G * pl.S + (q.copy_row1 - q.copy_row0 + 2 * kSortWaves - 1) / (2 * kSortWaves)));
+        return dim3((unsigned)(pl.G * pl.S + (q.copy_row1 - q.copy_row0 + kBigCopyRows * kSortWaves - 1) / (kBigCopyRows * kSortWaves)));
     };
     sp.stagger_wgs = g_stagger_wgs;
     sp.stagger_sleeps = g_stagger_sleeps;
     sp.copy_in = dense_in;
     sp.copy_out = dense_out;
     sp.d = d;
-    const size_t lds = (size_t)kSortWaves * pl.part * sizeof(uint32_t);
+    const size_t lds = (size_t)(kSortWaves + 2) * pl.part * sizeof(uint32_t);
     if (pl.S == 1) {
         const dim3 g1 = sort_grid(sp);
         hipLaunchKernelGGL(sort_kernel<SORT_FUSED>, g1, dim3(1024), lds, stream, sp, sh);
@@ -812,15 +817,14 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     rp.ncb = pl.ncb;
     rp.n_piece_items = pl.NB * pl.ncb;
     rp.count = sp.count;
-    rp.row_start = sp.row_start;
-    rp.srt_id = sp.srt_id;
-    rp.srt_addr = sp.srt_addr;
+    rp.sorted = sp.sorted;
+    rp.n = (int32_t)n;
     rp.n_valid = sp.n_valid;
     rp.dense_in = dense_in;
     rp.dense_out = dense_out;
     rp.partial = (float*)(ws + pl.off_partial);
     rp.n_cut = sp.n_cut;
-    rp.cut_list = (int2*)(ws + pl.off_cut_list);
+    rp.cut_list = (int4*)(ws + pl.off_cut_list);
     rp.copy_row0 = copy_done;
     rp.copy_row1 = tail0;
     const int64_t items = (int64_t)rp.n_piece_items + (in_place ? 0 : tail0 - copy_done);
@@ -847,7 +851,6 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
         cp.C = pl.C;
         cp.ncb = pl.ncb;
         cp.count = sp.count;
-        cp.row_start = sp.row_start;
         cp.n_cut = sp.n_cut;
         cp.cut_list = rp.cut_list;
         cp.dense_in = dense_in;
@@ -856,7 +859,7 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
         cp.groups = pl.NB < g_combine_groups ? pl.NB : g_combine_groups;
         cp.copy_row0 = tail0;
         cp.copy_row1 = V;
-        const unsigned cgrid = (unsigned)(cp.groups * pl.ncb + (V - tail0 + 2 * kSortWaves - 1) / (2 * kSortWaves));
+        const unsigned cgrid = (unsigned)(cp.groups * pl.ncb + (V - tail0 + kBigCopyRows * kSortWaves - 1) / (kBigCopyRows * kSortWaves));
         hipLaunchKernelGGL(combine_kernel, dim3(cgrid), dim3(1024), 0, stream, cp);
         if (hipGetLastError() != hipSuccess) return TS_ERR_HIP;
     }
@@ -986,14 +989,14 @@ int ts_bind_workspace(void* ws, int64_t bytes)
     return TS_OK;
 }
 
-int ts_last_views(const int32_t** count, const int32_t** row_start, const int32_t** perm,
+int ts_last_views(const int32_t** count, const int32_t** row_start, const void** sorted,
                   const int32_t** n_valid, const int32_t** n_bad_ids)
 {
     if (!g_ws || !g_have_last) return TS_ERR_WORKSPACE;
     const char* ws = (const char*)g_ws;
     if (count) *count = (const int32_t*)(ws + g_last_plan.off_count);
     if (row_start) *row_start = (const int32_t*)(ws + g_last_plan.off_row_start);
-    if (perm) *perm = (const int32_t*)(ws + g_last_plan.off_perm);
+    if (sorted) *sorted = (const void*)(ws + g_last_plan.off_sorted);
     if (n_valid) *n_valid = (const int32_t*)(ws + g_last_plan.off_nvalid);
     if (n_bad_ids) *n_bad_ids = (const int32_t*)(ws + g_last_plan.off_nbad);
     return TS_OK;
