@@ -167,7 +167,7 @@ int ts_set_stagger(int32_t work_groups, int32_t sleeps);
 /* Tuning.  Ids owned by one sort work-group (64 .. 1024, power of two; 0 = choose from V and n). */
 int ts_set_sort_part(int32_t part);
 
-/* Tuning.  Work-groups per column block that finish cut rows in the combine launch (default 128). */
+/* Tuning.  Work-groups per column block that finish cut rows in the combine launch (0 = choose). */
 int ts_set_combine_groups(int32_t groups);
 
 const char* ts_status_string(int status);

@@ -67,7 +67,7 @@ constexpr int kMaxSlices = 64;
 constexpr int kSliceTokens = 16384;
 constexpr int kFusedSortMax = 16384;   // up to here one launch sorts everything
 constexpr int kPieceSmallMax = 32768;  // up to here pieces of 16 positions, above 32
-constexpr int64_t kOverlapSortBytes = 112ll << 20;     // about what HBM moves while a sort launch runs
+constexpr int64_t kOverlapSortBytes = 96ll << 20;      // about what HBM moves while a sort launch runs
 constexpr int64_t kOverlapCombineBytes = 40ll << 20;   // same for the combine launch
 constexpr int kCombineGroups = 32;     // work-groups per column block in the combine kernel
 
@@ -112,13 +112,17 @@ __device__ __forceinline__ f4 load_row4(uint64_t row_addr, int col);
 template <>
 __device__ __forceinline__ f4 load_row4<float>(uint64_t row_addr, int col)
 {
-    return __builtin_nontemporal_load(reinterpret_cast<const f4*>(row_addr + (uint64_t)col * 4u));
+    // (the address arrives as an integer: say that it is global memory, or the compiler
+    // falls back to flat loads)
+    typedef const f4 __attribute__((address_space(1))) * global_f4;
+    return __builtin_nontemporal_load(reinterpret_cast<global_f4>(row_addr + (uint64_t)col * 4u));
 }
 
 template <>
 __device__ __forceinline__ f4 load_row4<uint16_t>(uint64_t row_addr, int col)
 {
-    u2 b = __builtin_nontemporal_load(reinterpret_cast<const u2*>(row_addr + (uint64_t)col * 2u));
+    typedef const u2 __attribute__((address_space(1))) * global_u2;
+    u2 b = __builtin_nontemporal_load(reinterpret_cast<global_u2>(row_addr + (uint64_t)col * 2u));
     f4 r;
     r.x = __uint_as_float(b.x << 16);
     r.y = __uint_as_float(b.x & 0xFFFF0000u);
@@ -231,17 +235,21 @@ enum { SORT_FUSED = 0, SORT_COUNT = 1, SORT_SCATTER = 2 };
 constexpr int kRoundTiles = 16;
 constexpr int kRoundPairs = kRoundTiles * 64;
 
-__device__ __forceinline__ void load_round(const ShardTable& sh, int j0, int j1, int a0, int b, int lane,
-                                           int32_t (&idr)[kRoundTiles])
+// ids0 / off0 describe shard j0; when the whole range lies in that shard (j0 == j1, the
+// common case) no table look-up is needed per tile.
+__device__ __forceinline__ void load_round(const ShardTable& sh, int j0, int j1, const int32_t* ids0, int off0,
+                                           int a0, int b, int lane, int32_t (&idr)[kRoundTiles])
 {
 #pragma unroll
     for (int u = 0; u < kRoundTiles; ++u) {
         // lanes past the end re-read the last pair, so that every load is unconditional
         // and all of them are in flight together; such lanes are masked where ids are used
         const int idx = min(a0 + u * 64 + lane, b - 1);
-        const int32_t* idp = sh.ids[j0];
-        uint64_t unused = 0;
-        locate(sh, j0, j1, idx, true, 0, idp, unused);
+        const int32_t* idp = ids0 + (idx - off0);
+        if (j0 != j1) {
+            uint64_t unused = 0;
+            locate(sh, j0, j1, idx, true, 0, idp, unused);
+        }
         idr[u] = *idp;
     }
 }
@@ -285,15 +293,19 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
     int j1 = j0;
     while (j1 < sh.k - 1 && sh.off[j1 + 1] < b) ++j1;
 
+    const int32_t* const ids0 = sh.ids[j0];
+    const char* const rows0 = sh.rows[j0];
+    const int off0 = sh.off[j0];
+
     int32_t idr[kRoundTiles];
-    if (rounds > 0) load_round(sh, j0, j1, a, b, lane, idr);
+    if (rounds > 0) load_round(sh, j0, j1, ids0, off0, a, b, lane, idr);
     __syncthreads();
 
     // pass 1: count owned pairs per (wavefront, id); count what lies below the part
     uint32_t below = 0, bad = 0;
     for (int r = 0; r < rounds; ++r) {
         const int a0 = a + r * kRoundPairs;
-        if (r > 0) load_round(sh, j0, j1, a0, b, lane, idr);
+        if (r > 0) load_round(sh, j0, j1, ids0, off0, a0, b, lane, idr);
 #pragma unroll
         for (int u = 0; u < kRoundTiles; ++u) {
             const bool valid = a0 + u * 64 + lane < b;
@@ -395,10 +407,9 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
     // consecutive sub-slices, so the sort is stable.  Per tile: one LDS read of the running
     // positions, a scalar loop over the distinct owned ids, one LDS write by the last lane
     // of each id.
-    volatile uint32_t* my = mycnt;
     for (int r = 0; r < rounds; ++r) {
         const int a0 = a + r * kRoundPairs;
-        if (rounds > 1) load_round(sh, j0, j1, a0, b, lane, idr);
+        if (rounds > 1) load_round(sh, j0, j1, ids0, off0, a0, b, lane, idr);
 #pragma unroll
         for (int u = 0; u < kRoundTiles; ++u) {
             if (a0 + u * 64 >= b) break;
@@ -409,7 +420,7 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
             const bool own = valid && rel < span;
             uint64_t m = ballot64(own);
             if (m == 0) continue;
-            const uint32_t basev = own ? my[rel] : 0u;
+            const uint32_t basev = own ? mycnt[rel] : 0u;
             const uint32_t tot_l = own ? id_total[rel] : 0u;
             const uint32_t rs_l = own ? id_start[rel] : 0u;
             uint32_t pos = 0, next = 0;
@@ -426,11 +437,16 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
                 }
                 m &= ~sm;
             }
-            if (leader) my[rel] = next;
+            if (leader) mycnt[rel] = next;
+            // lanes exchange running positions through LDS from one tile to the next: the
+            // hardware keeps a wavefront's LDS accesses in order, the compiler must too
+            asm volatile("" ::: "memory");
             if (own) {
-                const int32_t* idp = nullptr;
-                uint64_t row_addr = 0;
-                locate(sh, j0, j1, idx, valid, p.row_bytes, idp, row_addr);
+                uint64_t row_addr = (uint64_t)(uintptr_t)rows0 + (uint64_t)(idx - off0) * (uint64_t)p.row_bytes;
+                if (j0 != j1) {
+                    const int32_t* idp = nullptr;
+                    locate(sh, j0, j1, idx, valid, p.row_bytes, idp, row_addr);
+                }
                 u4* rec = reinterpret_cast<u4*>(p.sorted + pos);
                 u4 r0, r1;
                 r0.x = (uint32_t)row_addr;
@@ -673,7 +689,7 @@ int64_t g_overlap_sort = -1;            // dense bytes (read + write) copied bes
 int64_t g_overlap_combine = -1;         // same, beside the combine launch
 int32_t g_stagger_wgs = 256, g_stagger_sleeps = 0;
 int32_t g_part_override = 0;
-int32_t g_combine_groups = kCombineGroups;
+int32_t g_combine_groups = 0;           // 0 = choose from the number of pieces
 void* g_ws = nullptr;
 int64_t g_ws_bytes = 0;
 Plan g_last_plan;
@@ -713,8 +729,9 @@ void make_plan(int64_t n, int32_t d, int32_t V, Plan* pl)
     // ids per sort work-group: smaller parts shorten the sort (fewer owned pairs per tile),
     // but every sorting work-group holds half of a compute unit and slows the copy that
     // runs beside it; about 64 work-groups per slice measured best
+    // (with several slices the scan of every slice by every part dominates: largest parts)
     int part = kMaxPart;
-    while (part > kMinPart && (int64_t)((V + part - 1) / part) < 64) part >>= 1;
+    while (pl->S == 1 && part > kMinPart && (int64_t)((V + part - 1) / part) < 64) part >>= 1;
     if (g_part_override) part = g_part_override;
     pl->part = part;
     pl->G = (V + part - 1) / part;
@@ -777,7 +794,9 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
 
     const bool in_place = dense_in == dense_out;
     // rows copied by the sort launches: about as many bytes as HBM moves while a sort runs
-    const int64_t budget = g_overlap_sort >= 0 ? g_overlap_sort : kOverlapSortBytes;
+    // (a multi-slice sort keeps the whole GPU busy by itself, and with that many pairs a large
+    // share of the rows copied blindly would be overwritten: no blind copy then)
+    const int64_t budget = g_overlap_sort >= 0 ? g_overlap_sort : (pl.S == 1 ? kOverlapSortBytes : 0);
     int64_t rows_per_launch = in_place ? 0 : budget / ((int64_t)8 * d);
     rows_per_launch = rows_per_launch / (kBigCopyRows * kSortWaves) * (kBigCopyRows * kSortWaves);
     // rows copied by the combine launch, taken from the end
@@ -856,7 +875,8 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
         cp.dense_in = dense_in;
         cp.dense_out = dense_out;
         cp.partial = rp.partial;
-        cp.groups = pl.NB < g_combine_groups ? pl.NB : g_combine_groups;
+        const int want = g_combine_groups ? g_combine_groups : (pl.NB <= 1024 ? kCombineGroups : 4 * kCombineGroups);
+        cp.groups = pl.NB < want ? pl.NB : want;
         cp.copy_row0 = tail0;
         cp.copy_row1 = V;
         const unsigned cgrid = (unsigned)(cp.groups * pl.ncb + (V - tail0 + kBigCopyRows * kSortWaves - 1) / (kBigCopyRows * kSortWaves));
@@ -871,7 +891,7 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     g_last_info[3] = pl.S;
     g_last_info[4] = pl.part;
     g_last_info[5] = pl.NB;
-    g_last_info[6] = pl.NB > 0 ? (pl.NB < g_combine_groups ? pl.NB : g_combine_groups) : 0;
+    g_last_info[6] = g_combine_groups;
     g_last_info[7] = in_place ? 1 : 0;
     g_have_last = true;
     return TS_OK;
@@ -1064,7 +1084,7 @@ int ts_set_sort_part(int32_t part)
 
 int ts_set_combine_groups(int32_t groups)
 {
-    if (groups < 1 || groups > 65535) return TS_ERR_SHAPE;
+    if (groups < 0 || groups > 65535) return TS_ERR_SHAPE;
     g_combine_groups = groups;
     return TS_OK;
 }
