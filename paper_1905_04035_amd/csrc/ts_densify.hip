@@ -58,7 +58,7 @@ static_assert(sizeof(SortedPair) == 32, "two 16-byte accesses per record");
 constexpr int kMaxPart = 1024;     // most ids one sort work-group owns (LDS: 16 x part x 4 B)
 constexpr int kMinPart = 128;
 #ifndef TS_BIG_COPY_ROWS
-#define TS_BIG_COPY_ROWS 1
+#define TS_BIG_COPY_ROWS 2
 #endif
 constexpr int kBigCopyRows = TS_BIG_COPY_ROWS;   // rows per wavefront in the copying work-groups of 1024 threads
 constexpr int kSortWaves = 16;     // wavefronts per sort work-group
@@ -105,31 +105,51 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x, int lane)
     return x;
 }
 
-// Value rows: four consecutive columns per lane, widened to fp32.
-template <typename RowT>
-__device__ __forceinline__ f4 load_row4(uint64_t row_addr, int col);
+// Value rows: 4 * NV consecutive columns per lane, widened to fp32.  (The address arrives as
+// an integer: say that it is global memory, or the compiler falls back to flat loads.)
+template <typename RowT, int NV>
+struct RowLoad;
 
 template <>
-__device__ __forceinline__ f4 load_row4<float>(uint64_t row_addr, int col)
-{
-    // (the address arrives as an integer: say that it is global memory, or the compiler
-    // falls back to flat loads)
-    typedef const f4 __attribute__((address_space(1))) * global_f4;
-    return __builtin_nontemporal_load(reinterpret_cast<global_f4>(row_addr + (uint64_t)col * 4u));
-}
+struct RowLoad<float, 1> {
+    static __device__ __forceinline__ void load(uint64_t row_addr, int col, f4 (&out)[1])
+    {
+        typedef const f4 __attribute__((address_space(1))) * global_f4;
+        out[0] = __builtin_nontemporal_load(reinterpret_cast<global_f4>(row_addr + (uint64_t)col * 4u));
+    }
+};
 
-template <>
-__device__ __forceinline__ f4 load_row4<uint16_t>(uint64_t row_addr, int col)
+__device__ __forceinline__ f4 widen_bf16x4(uint32_t lo, uint32_t hi)
 {
-    typedef const u2 __attribute__((address_space(1))) * global_u2;
-    u2 b = __builtin_nontemporal_load(reinterpret_cast<global_u2>(row_addr + (uint64_t)col * 2u));
     f4 r;
-    r.x = __uint_as_float(b.x << 16);
-    r.y = __uint_as_float(b.x & 0xFFFF0000u);
-    r.z = __uint_as_float(b.y << 16);
-    r.w = __uint_as_float(b.y & 0xFFFF0000u);
+    r.x = __uint_as_float(lo << 16);
+    r.y = __uint_as_float(lo & 0xFFFF0000u);
+    r.z = __uint_as_float(hi << 16);
+    r.w = __uint_as_float(hi & 0xFFFF0000u);
     return r;
 }
+
+template <>
+struct RowLoad<uint16_t, 1> {
+    static __device__ __forceinline__ void load(uint64_t row_addr, int col, f4 (&out)[1])
+    {
+        typedef const u2 __attribute__((address_space(1))) * global_u2;
+        const u2 b = __builtin_nontemporal_load(reinterpret_cast<global_u2>(row_addr + (uint64_t)col * 2u));
+        out[0] = widen_bf16x4(b.x, b.y);
+    }
+};
+
+// bf16 rows with d % 8 == 0: one 16-byte load brings eight columns
+template <>
+struct RowLoad<uint16_t, 2> {
+    static __device__ __forceinline__ void load(uint64_t row_addr, int col, f4 (&out)[2])
+    {
+        typedef const u4 __attribute__((address_space(1))) * global_u4;
+        const u4 b = __builtin_nontemporal_load(reinterpret_cast<global_u4>(row_addr + (uint64_t)col * 2u));
+        out[0] = widen_bf16x4(b.x, b.y);
+        out[1] = widen_bf16x4(b.z, b.w);
+    }
+};
 
 __device__ __forceinline__ f4 load_f4(const float* p) { return *reinterpret_cast<const f4*>(p); }
 __device__ __forceinline__ void store_f4(float* p, f4 v) { *reinterpret_cast<f4*>(p) = v; }
@@ -480,7 +500,9 @@ struct ReduceParams {
     int4* cut_list;             // (row id, first piece, pieces, -) of every cut row, in no particular order
 };
 
-template <typename RowT>
+// NV: 16-byte fp32 vectors per lane (a wavefront item covers 256 * NV columns); BATCH: sorted
+// positions whose rows are loaded together.
+template <typename RowT, int NV, int BATCH>
 __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
 {
     const int lane = threadIdx.x & 63;
@@ -494,10 +516,10 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
         return;
     }
 
-    // ---- piece item: sorted positions [pos0, pos0 + C), columns [cb*256, cb*256 + 256)
+    // ---- piece item: sorted positions [pos0, pos0 + C), columns [cb*256*NV, (cb+1)*256*NV)
     const int k = item / p.ncb;
     const int cb = item - k * p.ncb;
-    const int col = cb * kColBlock + lane * 4;
+    const int col = (cb * kColBlock + lane * 4) * NV;
     const bool colok = col < p.d;
     const int C = p.C;
     const int pos0 = k * C;
@@ -540,36 +562,54 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
     const uint32_t slot = (uint32_t)(2 * k + (s >= pos0 ? 1 : 0));
     const bool have_dense = p.dense_in != nullptr;
 
-    f4 acc = (f4)(0.0f);
-    for (int base = a; base < b; base += 8) {
-        f4 r[8], dn[8];
+    f4 acc[NV];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+    for (int q = 0; q < NV; ++q) acc[q] = (f4)(0.0f);
+    for (int base = a; base < b; base += BATCH) {
+        f4 r[BATCH][NV], dn[BATCH][NV];
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
             const int j = base + u;
-            r[u] = (f4)(0.0f);
-            dn[u] = (f4)(0.0f);
+#pragma unroll
+            for (int q = 0; q < NV; ++q) {
+                r[u][q] = (f4)(0.0f);
+                dn[u][q] = (f4)(0.0f);
+            }
             if (j < b) {
                 const uint64_t ra = bcast64(addr, j);
-                if (colok) r[u] = load_row4<RowT>(ra, col);
+                if (colok) RowLoad<RowT, NV>::load(ra, col, r[u]);
                 if (have_dense && (((Lm & W) >> j) & 1ull)) {
                     const int vj = (int)bcast((uint32_t)id, j);
-                    if (colok) dn[u] = load_f4_stream(p.dense_in + (size_t)vj * p.d + col);
+                    if (colok) {
+#pragma unroll
+                        for (int q = 0; q < NV; ++q)
+                            dn[u][q] = load_f4_stream(p.dense_in + (size_t)vj * p.d + col + 4 * q);
+                    }
                 }
             }
         }
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < BATCH; ++u) {
             const int j = base + u;
             if (j < b) {
-                const f4 prev = ((F >> j) & 1ull) ? (f4)(0.0f) : acc;
-                acc = prev + r[u];
+                const bool fresh = (F >> j) & 1ull;
+#pragma unroll
+                for (int q = 0; q < NV; ++q) acc[q] = (fresh ? (f4)(0.0f) : acc[q]) + r[u][q];
                 if ((Lm >> j) & 1ull) {
                     if ((W >> j) & 1ull) {
                         const int vj = (int)bcast((uint32_t)id, j);
-                        if (colok) store_f4_stream(p.dense_out + (size_t)vj * p.d + col, acc + dn[u]);
+                        if (colok) {
+#pragma unroll
+                            for (int q = 0; q < NV; ++q)
+                                store_f4_stream(p.dense_out + (size_t)vj * p.d + col + 4 * q, acc[q] + dn[u][q]);
+                        }
                     } else {
                         const uint32_t sj = bcast(slot, j);
-                        if (colok) store_f4(p.partial + (size_t)sj * p.d + col, acc);
+                        if (colok) {
+#pragma unroll
+                            for (int q = 0; q < NV; ++q)
+                                store_f4(p.partial + (size_t)sj * p.d + col + 4 * q, acc[q]);
+                        }
                     }
                 }
             }
@@ -593,7 +633,7 @@ struct CombineParams {
 // Work-group (e, cb) finishes column block cb of the cut rows e, e + gridDim.x, ...
 // The P pieces of a row are split into 16 contiguous shares, one per wavefront, each
 // added in piece order; wavefront 0 then adds the shares in order and dense_in last.
-__global__ __launch_bounds__(1024) void combine_kernel(CombineParams p)
+__global__ __launch_bounds__(1024, 8) void combine_kernel(CombineParams p)
 {
     __shared__ f4 share[kSortWaves][64];
 
@@ -623,10 +663,10 @@ __global__ __launch_bounds__(1024) void combine_kernel(CombineParams p)
         const int j1 = min(P, j0 + per);
 
         f4 acc = (f4)(0.0f);
-        for (int jb = j0; jb < j1; jb += 16) {
-            f4 x[16];
+        for (int jb = j0; jb < j1; jb += 8) {
+            f4 x[8];
 #pragma unroll
-            for (int u = 0; u < 16; ++u) {
+            for (int u = 0; u < 8; ++u) {
                 const int j = jb + u;
                 x[u] = (f4)(0.0f);
                 if (j < j1 && colok) {
@@ -635,7 +675,7 @@ __global__ __launch_bounds__(1024) void combine_kernel(CombineParams p)
                 }
             }
 #pragma unroll
-            for (int u = 0; u < 16; ++u)
+            for (int u = 0; u < 8; ++u)
                 if (jb + u < j1) acc += x[u];
         }
         share[w][lane] = acc;
@@ -679,7 +719,7 @@ __global__ __launch_bounds__(1024) void unique_kernel(const int32_t* count, int 
 
 // ------------------------------------------------------------------ host side
 struct Plan {
-    int32_t S, SL, G, part, C, NB, ncb;
+    int32_t S, SL, G, part, C, NB, ncb;   // ncb: 256-column blocks of a row
     size_t off_nvalid, off_nbad, off_ncut, off_cut_list, off_count, off_row_start, off_sorted, off_tot,
         off_below, off_bad, off_partial, total;
 };
@@ -833,8 +873,9 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     rp.V = V;
     rp.d = d;
     rp.C = pl.C;
-    rp.ncb = pl.ncb;
-    rp.n_piece_items = pl.NB * pl.ncb;
+    const bool wide = row_dtype == TS_ROW_BF16 && (d % 8) == 0;     // 16-byte loads of bf16 rows
+    rp.ncb = wide ? (d + 2 * kColBlock - 1) / (2 * kColBlock) : pl.ncb;
+    rp.n_piece_items = pl.NB * rp.ncb;
     rp.count = sp.count;
     rp.sorted = sp.sorted;
     rp.n = (int32_t)n;
@@ -852,10 +893,12 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     const bool prof = g_prof_used < g_prof_cap;
     if (prof && hipEventRecord(g_ev[2 * g_prof_used], stream) != hipSuccess) return TS_ERR_HIP;
     if (rgrid > 0) {
-        if (row_dtype == TS_ROW_BF16)
-            hipLaunchKernelGGL(reduce_kernel<uint16_t>, dim3(rgrid), dim3(256), 0, stream, rp);
+        if (wide)
+            hipLaunchKernelGGL((reduce_kernel<uint16_t, 2, 4>), dim3(rgrid), dim3(256), 0, stream, rp);
+        else if (row_dtype == TS_ROW_BF16)
+            hipLaunchKernelGGL((reduce_kernel<uint16_t, 1, 8>), dim3(rgrid), dim3(256), 0, stream, rp);
         else
-            hipLaunchKernelGGL(reduce_kernel<float>, dim3(rgrid), dim3(256), 0, stream, rp);
+            hipLaunchKernelGGL((reduce_kernel<float, 1, 8>), dim3(rgrid), dim3(256), 0, stream, rp);
     }
     if (prof) {
         if (hipEventRecord(g_ev[2 * g_prof_used + 1], stream) != hipSuccess) return TS_ERR_HIP;

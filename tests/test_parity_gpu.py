@@ -86,6 +86,16 @@ def test_ragged_shapes(V, d, n):
     _case(w)
 
 
+@pytest.mark.parametrize("V,d,n", [(700, 260, 3000), (700, 264, 3000), (64, 8, 500), (3000, 1536, 40000)])
+def test_bf16_rows_narrow_and_wide_loads(V, d, n):
+    # d % 8 == 0 takes 16-byte row loads, otherwise 8-byte ones
+    w = wl.make_custom(V=V, d=d, n_list=[n // 2, n - n // 2], zipf_s=1.3, seed=V + d, row_dtype=wl.ROW_BF16)
+    _case(w, mode="multi")
+    wi = wl.make_custom(V=V, d=d, n_list=[n], zipf_s=1.3, seed=V + d + 1, row_dtype=wl.ROW_BF16,
+                        integer_values=True)
+    _case(wi, mode="single", exact_bits=True)
+
+
 @pytest.mark.parametrize("piece", [8, 16, 32])
 def test_piece_sizes_and_exact_boundaries(piece):
     ts.ts_set_piece_tokens(piece)
