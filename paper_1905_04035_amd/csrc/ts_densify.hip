@@ -430,7 +430,9 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
     for (int r = 0; r < rounds; ++r) {
         const int a0 = a + r * kRoundPairs;
         if (rounds > 1) load_round(sh, j0, j1, ids0, off0, a0, b, lane, idr);
-#pragma unroll
+        // (not unrolled: one copy of the body keeps the kernel within 64 registers; the
+        // wave-uniform index into idr becomes a relative register move)
+#pragma unroll 1
         for (int u = 0; u < kRoundTiles; ++u) {
             if (a0 + u * 64 >= b) break;
             const int idx = a0 + u * 64 + lane;
