@@ -164,13 +164,6 @@ int ts_set_piece_tokens(int32_t piece_tokens);
 int ts_set_overlap_bytes(int64_t sort_bytes, int64_t combine_bytes);
 int ts_set_stagger(int32_t work_groups, int32_t sleeps);
 
-/*
- * Tuning.  pieces: consecutive pieces of a very long row that one wavefront item sums into a
- * single partial row (1 = never, 2, 4 or 8; 0 = choose from n).  Changes the fixed summation
- * order (still deterministic).
- */
-int ts_set_super_pieces(int32_t pieces);
-
 /* Tuning.  Ids owned by one sort work-group (64 .. 1024, power of two; 0 = choose from V and n). */
 int ts_set_sort_part(int32_t part);
 

@@ -53,15 +53,13 @@ def lib():
         l.ts_set_overlap_bytes.argtypes = [i64, i64]
         l.ts_set_stagger.argtypes = [i32, i32]
         l.ts_set_sort_part.argtypes = [i32]
-        l.ts_set_super_pieces.argtypes = [i32]
         l.ts_set_combine_groups.argtypes = [i32]
         l.ts_status_string.argtypes = [C.c_int]
         l.ts_status_string.restype = C.c_char_p
         for name in ("ts_densify", "ts_densify_bf16", "ts_densify_multi", "ts_buffer_bytes",
                      "ts_workspace_bytes", "ts_bind_workspace", "ts_last_views", "ts_unique_ids",
                      "ts_last_launch_info",
-                     "ts_profile_begin", "ts_profile_end", "ts_set_piece_tokens", "ts_set_overlap_bytes", "ts_set_stagger", "ts_set_sort_part", "ts_set_combine_groups",
-                     "ts_set_super_pieces"):
+                     "ts_profile_begin", "ts_profile_end", "ts_set_piece_tokens", "ts_set_overlap_bytes", "ts_set_stagger", "ts_set_sort_part", "ts_set_combine_groups"):
             getattr(l, name).restype = C.c_int
         _lib = l
     return _lib
@@ -253,7 +251,3 @@ def ts_set_sort_part(part: int) -> None:
 
 def ts_set_combine_groups(groups: int) -> None:
     _check(lib().ts_set_combine_groups(groups), "ts_set_combine_groups")
-
-
-def ts_set_super_pieces(pieces: int) -> None:
-    _check(lib().ts_set_super_pieces(pieces), "ts_set_super_pieces")

@@ -489,7 +489,6 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
 // ------------------------------------------------------------------ reduce
 struct ReduceParams {
     int32_t V, d, C, ncb;
-    int32_t SB;                 // pieces per super-piece of a very long row (1 = none)
     int32_t n_piece_items;      // pieces x column blocks
     int32_t copy_row0, copy_row1;   // copy items cover the untouched rows in this range
     const int32_t* count;
@@ -500,7 +499,7 @@ struct ReduceParams {
     float* dense_out;
     float* partial;             // [2 * pieces][d]
     int32_t* n_cut;             // number of cut rows found so far
-    int4* cut_list;             // (row id, first piece, row_start, count) of every cut row, in no particular order
+    int4* cut_list;             // (row id, first piece, pieces, -) of every cut row, in no particular order
 };
 
 // NV: 16-byte fp32 vectors per lane (a wavefront item covers 256 * NV columns); BATCH: sorted
@@ -558,68 +557,12 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
     // a cut row is announced once, by the item that holds its first pair
     if (cb == 0 && active && !whole && wpos == s) {
         const int e = atomicAdd(p.n_cut, 1);
-        p.cut_list[e] = make_int4(id, k, s, c);
-    }
-    const bool have_dense = p.dense_in != nullptr;
-
-    // A row that covers SB whole consecutive pieces (an aligned "super-block") gets ONE partial
-    // row for them, written by the first of the SB items; the other SB - 1 items do nothing.
-    // Inside, every piece is summed in order and the piece sums are added in order.
-    if (p.SB > 1) {
-        const int c0 = (int)bcast((uint32_t)c, 0), s0 = (int)bcast((uint32_t)s, 0);
-        const int kf = k / p.SB * p.SB;
-        const int sp0 = kf * C, sp1 = sp0 + p.SB * C;
-        if (c0 > C && s0 <= sp0 && s0 + c0 >= sp1) {
-            if (k != kf) return;
-            f4 tot[NV];
-#pragma unroll
-            for (int q = 0; q < NV; ++q) tot[q] = (f4)(0.0f);
-            for (int blk = 0; blk < p.SB; ++blk) {
-                // records of this piece: lane j holds position sp0 + blk * C + j
-                uint64_t baddr = addr;
-                if (blk > 0) {
-                    baddr = 0;
-                    if (lane < C) {
-                        const u4* rec = reinterpret_cast<const u4*>(p.sorted + sp0 + blk * C + lane);
-                        const u4 q0 = rec[0];
-                        baddr = ((uint64_t)q0.y << 32) | q0.x;
-                    }
-                }
-                f4 acc[NV];
-#pragma unroll
-                for (int q = 0; q < NV; ++q) acc[q] = (f4)(0.0f);
-                for (int base = 0; base < C; base += BATCH) {
-                    f4 r[BATCH][NV];
-#pragma unroll
-                    for (int u = 0; u < BATCH; ++u) {
-#pragma unroll
-                        for (int q = 0; q < NV; ++q) r[u][q] = (f4)(0.0f);
-                        if (base + u < C) {
-                            const uint64_t ra = bcast64(baddr, base + u);
-                            if (colok) RowLoad<RowT, NV>::load(ra, col, r[u]);
-                        }
-                    }
-#pragma unroll
-                    for (int u = 0; u < BATCH; ++u)
-                        if (base + u < C) {
-#pragma unroll
-                            for (int q = 0; q < NV; ++q) acc[q] += r[u][q];
-                        }
-                }
-#pragma unroll
-                for (int q = 0; q < NV; ++q) tot[q] += acc[q];
-            }
-            const size_t sj = (size_t)(2 * kf + (s0 >= sp0 ? 1 : 0));
-            if (colok) {
-#pragma unroll
-                for (int q = 0; q < NV; ++q) store_f4(p.partial + sj * p.d + col + 4 * q, tot[q]);
-            }
-            return;
-        }
+        p.cut_list[e] = make_int4(id, k, (s + c - 1) / C - k + 1, 0);
     }
     const int a = __builtin_ctzll(A);
     const int b = 64 - __builtin_clzll(A);
     const uint32_t slot = (uint32_t)(2 * k + (s >= pos0 ? 1 : 0));
+    const bool have_dense = p.dense_in != nullptr;
 
     f4 acc[NV];
 #pragma unroll
@@ -679,7 +622,6 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
 // ------------------------------------------------------------------ combine
 struct CombineParams {
     int32_t V, d, C, ncb;
-    int32_t SB;                 // pieces per super-piece (1 = none)
     const int32_t* count;
     const int32_t* n_cut;
     const int4* cut_list;
@@ -715,18 +657,7 @@ __global__ __launch_bounds__(1024, 8) void combine_kernel(CombineParams p)
     for (int e = e0; e < ncut; e += p.groups) {
         if (e != e0) ent = p.cut_list[e];
         const int v = ent.x, k = ent.y;
-        // partial rows of this row, in order: H single pieces, M super-pieces (one partial row per
-        // SB pieces), T single pieces
-        const int C = p.C;
-        const int rs = ent.z, rc = ent.w;
-        const int k1 = (rs + rc - 1) / C;
-        const int SBC = p.SB * C;
-        const int sb_lo = (rs + SBC - 1) / SBC, sb_hi = (rs + rc) / SBC;
-        const bool supers = p.SB > 1 && sb_hi > sb_lo;
-        const int H = supers ? sb_lo * p.SB - k : k1 - k + 1;
-        const int M = supers ? sb_hi - sb_lo : 0;
-        const int T = supers ? k1 - sb_hi * p.SB + 1 : 0;
-        const int P = H + M + T;                    // >= 1
+        const int P = ent.z;                        // pieces of this row, >= 2
         f4 dn = (f4)(0.0f);
         if (w == 0 && colok && p.dense_in) dn = load_f4_stream(p.dense_in + (size_t)v * p.d + col);
         const int per = (P + kSortWaves - 1) / kSortWaves;
@@ -741,8 +672,7 @@ __global__ __launch_bounds__(1024, 8) void combine_kernel(CombineParams p)
                 const int j = jb + u;
                 x[u] = (f4)(0.0f);
                 if (j < j1 && colok) {
-                    const int kb = j < H ? k + j : (j < H + M ? (sb_lo + (j - H)) * p.SB : sb_hi * p.SB + (j - H - M));
-                    const size_t sl = (kb == k) ? (size_t)(2 * k + 1) : (size_t)(2 * kb);
+                    const size_t sl = (j == 0) ? (size_t)(2 * k + 1) : (size_t)(2 * (k + j));
                     x[u] = load_f4(p.partial + sl * p.d + col);
                 }
             }
@@ -791,7 +721,7 @@ __global__ __launch_bounds__(1024) void unique_kernel(const int32_t* count, int 
 
 // ------------------------------------------------------------------ host side
 struct Plan {
-    int32_t S, SL, G, part, C, SB, NB, ncb;   // ncb: 256-column blocks of a row
+    int32_t S, SL, G, part, C, NB, ncb;   // ncb: 256-column blocks of a row
     size_t off_nvalid, off_nbad, off_ncut, off_cut_list, off_count, off_row_start, off_sorted, off_tot,
         off_below, off_bad, off_partial, total;
 };
@@ -801,7 +731,6 @@ int64_t g_overlap_sort = -1;            // dense bytes (read + write) copied bes
 int64_t g_overlap_combine = -1;         // same, beside the combine launch
 int32_t g_stagger_wgs = 256, g_stagger_sleeps = 0;
 int32_t g_part_override = 0;
-int32_t g_super_override = 0;
 int32_t g_combine_groups = 0;           // 0 = choose from the number of pieces
 void* g_ws = nullptr;
 int64_t g_ws_bytes = 0;
@@ -849,7 +778,6 @@ void make_plan(int64_t n, int32_t d, int32_t V, Plan* pl)
     pl->part = part;
     pl->G = (V + part - 1) / part;
     pl->C = piece_tokens_for(n);
-    pl->SB = g_super_override ? g_super_override : (n > kPieceSmallMax ? 4 : 1);
     pl->NB = (int32_t)((n + pl->C - 1) / pl->C);
     pl->ncb = (d + kColBlock - 1) / kColBlock;
     size_t o = 0;
@@ -947,7 +875,6 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     rp.V = V;
     rp.d = d;
     rp.C = pl.C;
-    rp.SB = pl.SB;
     const bool wide = row_dtype == TS_ROW_BF16 && (d % 8) == 0;     // 16-byte loads of bf16 rows
     rp.ncb = wide ? (d + 2 * kColBlock - 1) / (2 * kColBlock) : pl.ncb;
     rp.n_piece_items = pl.NB * rp.ncb;
@@ -986,7 +913,6 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
         cp.V = V;
         cp.d = d;
         cp.C = pl.C;
-        cp.SB = pl.SB;
         cp.ncb = pl.ncb;
         cp.count = sp.count;
         cp.n_cut = sp.n_cut;
@@ -1191,13 +1117,6 @@ int ts_set_overlap_bytes(int64_t sort_bytes, int64_t combine_bytes)
     if (sort_bytes < -1 || combine_bytes < -1) return TS_ERR_SHAPE;
     g_overlap_sort = sort_bytes;
     g_overlap_combine = combine_bytes;
-    return TS_OK;
-}
-
-int ts_set_super_pieces(int32_t pieces)
-{
-    if (pieces != 0 && pieces != 1 && pieces != 2 && pieces != 4 && pieces != 8) return TS_ERR_SHAPE;
-    g_super_override = pieces;
     return TS_OK;
 }
 

@@ -106,8 +106,6 @@ def test_tuning_setters_validate(lib):
     assert lib.ts_set_combine_groups(-1) == ts.TS_ERR_SHAPE
     assert lib.ts_set_combine_groups(0) == ts.TS_OK
     assert lib.ts_set_stagger(256, 0) == ts.TS_OK
-    assert lib.ts_set_super_pieces(3) == ts.TS_ERR_SHAPE
-    assert lib.ts_set_super_pieces(0) == ts.TS_OK
 
 
 def test_status_strings(lib):

@@ -115,31 +115,6 @@ def test_piece_sizes_and_exact_boundaries(piece):
         ts.ts_set_piece_tokens(0)
 
 
-@pytest.mark.parametrize("sb", [1, 2, 4, 8])
-@pytest.mark.parametrize("piece", [8, 32])
-def test_super_pieces_of_very_long_rows(sb, piece):
-    # rows long enough to cover whole aligned groups of `sb` pieces, starting at every offset
-    ts.ts_set_piece_tokens(piece)
-    ts.ts_set_super_pieces(sb)
-    try:
-        V, d = 40, 256
-        span = sb * piece
-        counts = [span, 1, 2 * span, 3, 3 * span + 1, piece - 1, span - 1, 5 * span + piece + 2, 2, 4 * span]
-        ids = np.concatenate([np.full(c, 2 + 3 * i, dtype=np.int32) for i, c in enumerate(counts)])
-        rng = np.random.default_rng(sb * 100 + piece)
-        ids = ids[rng.permutation(len(ids))]
-        rows = rng.integers(-4, 5, size=(len(ids), d)).astype(np.float32)
-        dense = rng.integers(-4, 5, size=(V, d)).astype(np.float32)
-        w = wl.Workload(spec=wl.Spec("custom", -1, V, d, 1, 0, "zipf"), ids=[ids], rows=[rows], dense_in=dense)
-        _case(w, exact_bits=True)
-        _case(wl.make_custom(V=300, d=512, n_list=[20000, 15000], zipf_s=1.6, seed=sb + piece), mode="multi")
-        _case(wl.make_custom(V=300, d=264, n_list=[30000], zipf_s=1.6, seed=sb + piece + 1,
-                             row_dtype=wl.ROW_BF16))
-    finally:
-        ts.ts_set_piece_tokens(0)
-        ts.ts_set_super_pieces(0)
-
-
 @pytest.mark.parametrize("mib", [0, 1, 4096])
 def test_result_does_not_depend_on_the_overlapped_copy(mib):
     w = wl.make_custom(V=5000, d=512, n_list=[6000, 3000], seed=46)
