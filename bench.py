@@ -29,7 +29,7 @@ HBM_PEAK_GBPS = 8000.0
 # factors a plain copy of known size gives).  Only valid for the kernel source it was taken
 # with: when the source's hash differs, `traffic` is reported as null.
 COUNTED_TRAFFIC = {
-    "source_sha256": "79f46d8145bbdfc1758a04a34f8ab3f3985bb43b652d9132d4a1fb03b490ad2b",
+    "source_sha256": "0d3da0aa549a27d0dd5cfb087e9aa2b7d0d0eca8001dea0c1c3081238db0c1ec",
     "workload": "transformer_big",
     "reduce_kernel_bytes_per_launch": 212.68e6,
 }
@@ -52,7 +52,6 @@ def main():
     ap.add_argument("--overlap-mib", type=float, default=-1.0,
                     help="dense bytes copied beside each sort launch (tuning; -1 = library default)")
     ap.add_argument("--overlap-combine-mib", type=float, default=-1.0, help="tuning; -1 = library default")
-    ap.add_argument("--stagger", type=int, nargs=2, default=None, metavar=("WGS", "SLEEPS"), help="tuning")
     ap.add_argument("--piece-tokens", type=int, default=0, help="tuning; 0 = library default")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run the same launches with n = 0: a plain [V, d] copy of known size, used to "
@@ -78,8 +77,6 @@ def main():
     if args.overlap_mib >= 0 or args.overlap_combine_mib >= 0:
         ts.ts_set_overlap_bytes(int(args.overlap_mib * (1 << 20)) if args.overlap_mib >= 0 else -1,
                                 int(args.overlap_combine_mib * (1 << 20)) if args.overlap_combine_mib >= 0 else -1)
-    if args.stagger:
-        ts.ts_set_stagger(args.stagger[0], args.stagger[1])
     if args.piece_tokens:
         ts.ts_set_piece_tokens(args.piece_tokens)
 
@@ -186,8 +183,7 @@ def main():
     alg_reduce = n * elem * d + 2 * 4 * d * (whole + untouched_mid)
     roofline = None
     traffic = None
-    default_tuning = (args.overlap_mib < 0 and args.overlap_combine_mib < 0 and not args.stagger
-                      and not args.piece_tokens)
+    default_tuning = (args.overlap_mib < 0 and args.overlap_combine_mib < 0 and not args.piece_tokens)
     if default_tuning and args.workload == COUNTED_TRAFFIC["workload"]:
         import hashlib
         src = os.path.join(ROOT, "paper_1905_04035_amd", "csrc", "ts_densify.hip")

@@ -156,13 +156,10 @@ int ts_set_piece_tokens(int32_t piece_tokens);
  * dense rows run beside them to keep HBM busy.  sort_bytes: dense bytes (read + write)
  * copied from dense_in to dense_out beside each sort launch, before it is known which
  * rows receive pairs (those are overwritten afterwards).  combine_bytes: the same beside
- * the combine launch (untouched rows only).  -1 = default, 0 = none.  ts_set_stagger
- * makes the first `work_groups` copying work-groups of a sort launch wait `sleeps` x 0.85
- * microseconds, so that the sort's own first loads are not queued behind the copy.
- * Results do not depend on any of these.
+ * the combine launch (untouched rows only).  -1 = default, 0 = none.  Results do not
+ * depend on them.
  */
 int ts_set_overlap_bytes(int64_t sort_bytes, int64_t combine_bytes);
-int ts_set_stagger(int32_t work_groups, int32_t sleeps);
 
 /* Tuning.  Ids owned by one sort work-group (64 .. 1024, power of two; 0 = choose from V and n). */
 int ts_set_sort_part(int32_t part);

@@ -51,7 +51,6 @@ def lib():
         l.ts_profile_end.argtypes = [vp, i32, vp]
         l.ts_set_piece_tokens.argtypes = [i32]
         l.ts_set_overlap_bytes.argtypes = [i64, i64]
-        l.ts_set_stagger.argtypes = [i32, i32]
         l.ts_set_sort_part.argtypes = [i32]
         l.ts_set_combine_groups.argtypes = [i32]
         l.ts_status_string.argtypes = [C.c_int]
@@ -59,7 +58,7 @@ def lib():
         for name in ("ts_densify", "ts_densify_bf16", "ts_densify_multi", "ts_buffer_bytes",
                      "ts_workspace_bytes", "ts_bind_workspace", "ts_last_views", "ts_unique_ids",
                      "ts_last_launch_info",
-                     "ts_profile_begin", "ts_profile_end", "ts_set_piece_tokens", "ts_set_overlap_bytes", "ts_set_stagger", "ts_set_sort_part", "ts_set_combine_groups"):
+                     "ts_profile_begin", "ts_profile_end", "ts_set_piece_tokens", "ts_set_overlap_bytes", "ts_set_sort_part", "ts_set_combine_groups"):
             getattr(l, name).restype = C.c_int
         _lib = l
     return _lib
@@ -239,10 +238,6 @@ def ts_set_piece_tokens(piece_tokens: int) -> None:
 
 def ts_set_overlap_bytes(sort_bytes: int, combine_bytes: int = -1) -> None:
     _check(lib().ts_set_overlap_bytes(sort_bytes, combine_bytes), "ts_set_overlap_bytes")
-
-
-def ts_set_stagger(work_groups: int, sleeps: int) -> None:
-    _check(lib().ts_set_stagger(work_groups, sleeps), "ts_set_stagger")
 
 
 def ts_set_sort_part(part: int) -> None:

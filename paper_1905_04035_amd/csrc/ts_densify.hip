@@ -243,7 +243,6 @@ struct SortParams {
     const float* copy_in;
     float* copy_out;
     int32_t copy_row0, copy_row1, d;
-    int32_t stagger_wgs, stagger_sleeps;   // the first copy work-groups start a little later
 };
 
 enum { SORT_FUSED = 0, SORT_COUNT = 1, SORT_SCATTER = 2 };
@@ -285,10 +284,7 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nsort = p.G * p.S;
     if ((int)blockIdx.x >= nsort) {
-        // Let the sort's own first loads (the ids) reach memory before the copy saturates it.
         const int cw = (int)blockIdx.x - nsort;
-        if (cw < p.stagger_wgs)
-            for (int i = 0; i < p.stagger_sleeps; ++i) __builtin_amdgcn_s_sleep(32);
         const int v = p.copy_row0 + (cw * kSortWaves + w) * kBigCopyRows;
         copy_rows<false, kBigCopyRows>(p.copy_in, p.copy_out, nullptr, v, p.copy_row1, p.d, lane);
         return;
@@ -729,7 +725,6 @@ struct Plan {
 int g_piece_override = 0;
 int64_t g_overlap_sort = -1;            // dense bytes (read + write) copied beside each sort launch; -1 = default
 int64_t g_overlap_combine = -1;         // same, beside the combine launch
-int32_t g_stagger_wgs = 256, g_stagger_sleeps = 0;
 int32_t g_part_override = 0;
 int32_t g_combine_groups = 0;           // 0 = choose from the number of pieces
 void* g_ws = nullptr;
@@ -854,8 +849,6 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
         copy_done = q.copy_row1;
         return dim3((unsigned)(pl.G * pl.S + (q.copy_row1 - q.copy_row0 + kBigCopyRows * kSortWaves - 1) / (kBigCopyRows * kSortWaves)));
     };
-    sp.stagger_wgs = g_stagger_wgs;
-    sp.stagger_sleeps = g_stagger_sleeps;
     sp.copy_in = dense_in;
     sp.copy_out = dense_out;
     sp.d = d;
@@ -1131,14 +1124,6 @@ int ts_set_combine_groups(int32_t groups)
 {
     if (groups < 0 || groups > 65535) return TS_ERR_SHAPE;
     g_combine_groups = groups;
-    return TS_OK;
-}
-
-int ts_set_stagger(int32_t work_groups, int32_t sleeps)
-{
-    if (work_groups < 0 || sleeps < 0 || sleeps > 64) return TS_ERR_SHAPE;
-    g_stagger_wgs = work_groups;
-    g_stagger_sleeps = sleeps;
     return TS_OK;
 }
 

@@ -105,7 +105,6 @@ def test_tuning_setters_validate(lib):
     assert lib.ts_set_overlap_bytes(-1, -1) == ts.TS_OK
     assert lib.ts_set_combine_groups(-1) == ts.TS_ERR_SHAPE
     assert lib.ts_set_combine_groups(0) == ts.TS_OK
-    assert lib.ts_set_stagger(256, 0) == ts.TS_OK
 
 
 def test_status_strings(lib):

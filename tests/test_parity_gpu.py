@@ -120,7 +120,6 @@ def test_result_does_not_depend_on_the_overlapped_copy(mib):
     w = wl.make_custom(V=5000, d=512, n_list=[6000, 3000], seed=46)
     ref = run_gpu(w, mode="multi")
     ts.ts_set_overlap_bytes(mib << 20, (mib // 2) << 20)
-    ts.ts_set_stagger(7, 2)
     try:
         _case(w, mode="multi")
         got = run_gpu(w, mode="multi")
@@ -129,7 +128,6 @@ def test_result_does_not_depend_on_the_overlapped_copy(mib):
         _case(wb)
     finally:
         ts.ts_set_overlap_bytes(-1, -1)
-        ts.ts_set_stagger(256, 0)
     assert np.array_equal(ref["out"].view(np.uint32), got["out"].view(np.uint32))
 
 
@@ -181,6 +179,37 @@ def test_runs_are_bit_identical():
     c = run_gpu(w, mode="multi")
     assert np.array_equal(a["out"].view(np.uint32), b["out"].view(np.uint32))
     assert np.array_equal(a["out"].view(np.uint32), c["out"].view(np.uint32))
+
+
+def test_a_call_can_be_captured_in_a_hip_graph_and_replayed():
+    # the call enqueues kernels only (no allocation, no host synchronisation, no memset), so it
+    # can be recorded once and replayed; every replay must give the eager call's bits
+    w = wl.make_custom(V=6000, d=512, n_list=[9000, 5000], zipf_s=1.3, seed=48)
+    ids, rows = w.concatenated()
+    ids_d, rows_d, dn = to_dev(ids), to_dev(rows), to_dev(w.dense_in)
+    eager = torch.empty_like(dn)
+    out = torch.zeros_like(dn)
+    ws = ts.Workspace(w.n_total, w.d, w.V, DEV)
+    try:
+        ts.ts_densify(ids_d, rows_d, w.d, w.V, dn, eager)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            ts.ts_densify(ids_d, rows_d, w.d, w.V, dn, out)
+        for rep in range(3):
+            out.zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out, eager), f"replay {rep} differs from the eager call"
+            # eager work between replays, through the same workspace
+            other = torch.empty_like(dn)
+            ts.ts_densify(ids_d[: 100 * (rep + 1)], rows_d[: 100 * (rep + 1)], w.d, w.V, dn, other)
+            torch.cuda.synchronize()
+        r = run_oracle(w)
+        assert np.all(np.abs(out.cpu().numpy().astype(np.float64) - r.exact) <= TOL * r.abs_sum)
+    finally:
+        ws.close()
 
 
 def test_dense_gradient_fed_as_slices():
