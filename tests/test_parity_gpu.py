@@ -86,6 +86,33 @@ def test_ragged_shapes(V, d, n):
     _case(w)
 
 
+def test_more_than_a_million_pairs_walks_each_slice_in_several_rounds():
+    # above 64 slices of 16384 pairs the slices grow, and a wavefront walks its share in
+    # several rounds of 1024 pairs
+    w = wl.make_custom(V=5000, d=8, n_list=[700001, 500000], zipf_s=1.2, seed=51, integer_values=True)
+    _case(w, mode="multi", exact_bits=True)
+
+
+def test_sixty_four_ragged_shards():
+    rng = np.random.default_rng(52)
+    n_list = [int(x) for x in rng.integers(0, 700, size=64)]
+    n_list[5] = 0
+    n_list[63] = 1
+    w = wl.make_custom(V=2000, d=64, n_list=n_list, zipf_s=1.1, seed=52)
+    _case(w, mode="multi")
+    # one shard more than the library accepts
+    dn = to_dev(w.dense_in)
+    with pytest.raises(ts.TsError) as e:
+        ts.ts_densify_multi([to_dev(w.ids[0])] * 65, [to_dev(w.rows[0])] * 65, wl.ROW_FP32, w.d, w.V, dn,
+                            torch.empty_like(dn))
+    assert e.value.status == ts.TS_ERR_SHAPE
+
+
+def test_huge_vocabulary_few_pairs_and_wide_rows():
+    _case(wl.make_custom(V=1000003, d=4, n_list=[50000], zipf_s=1.05, seed=53))
+    _case(wl.make_custom(V=37, d=8192, n_list=[300], zipf_s=1.3, seed=54))
+
+
 @pytest.mark.parametrize("V,d,n", [(700, 260, 3000), (700, 264, 3000), (64, 8, 500), (3000, 1536, 40000)])
 def test_bf16_rows_narrow_and_wide_loads(V, d, n):
     # d % 8 == 0 takes 16-byte row loads, otherwise 8-byte ones
