@@ -56,6 +56,10 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run the same launches with n = 0: a plain [V, d] copy of known size, used to "
                          "scale hardware byte counters")
+    ap.add_argument("--compare-rules", action="store_true",
+                    help="time ts_accumulate under Algorithm 1 (gather) and Algorithm 2 (convert and reduce) "
+                         "on the workload's three gradients and print both buffers' sizes (Fig. 5 of the "
+                         "paper, for one worker)")
     ap.add_argument("--no-events", action="store_true",
                     help="do not record per-kernel HIP events inside the timed region")
     args = ap.parse_args()
@@ -118,6 +122,41 @@ def main():
                                                 "reduce_kernel": {"read_bytes": 4 * d * (V - x),
                                                                   "write_bytes": 4 * d * (V - x)}},
                           "steps": args.warmup + args.steps}))
+        ws.close()
+        return
+
+    if args.compare_rules:
+        assert not multi and elem == 4, "--compare-rules takes a two-contribution fp32 workload"
+        n0 = len(w.ids[0])
+        res = {}
+        for rule, name in ((ts.TS_RULE_TF, "algorithm_1_gather"), (ts.TS_RULE_PROPOSED, "algorithm_2_convert_and_reduce")):
+            outs = [dict(ids=torch.empty(V + n, dtype=torch.int32, device=dev),
+                         rows=torch.empty((V + n, d), dtype=torch.float32, device=dev)) for _ in sets] \
+                if rule == ts.TS_RULE_TF else [None] * len(sets)
+
+            def acc_step(i):
+                s = sets[i % len(sets)]
+                grads = [("slices", s["ids"][:n0], s["rows"][:n0]), ("slices", s["ids"][n0:], s["rows"][n0:]),
+                         ("dense", s["dense_in"])]
+                o = outs[i % len(sets)]
+                return ts.ts_accumulate(grads, rule, d, V, s["dense_out"], o and o["ids"], o and o["rows"], stream)
+
+            for i in range(args.warmup):
+                st, total = acc_step(i)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(args.steps):
+                acc_step(i)
+            torch.cuda.synchronize()
+            us = (time.perf_counter() - t0) * 1e6 / args.steps
+            out_bytes = total * (4 + 4 * d) if total is not None else 4 * V * d
+            res[name] = {"strategy": st, "accumulate_buffer_bytes": out_bytes, "us_per_call": round(us, 2)}
+        a, b = res["algorithm_1_gather"], res["algorithm_2_convert_and_reduce"]
+        print(json.dumps({"comparison": "tensor accumulate, sparse gather vs dense reduce, one worker",
+                          "workload": args.workload, "V": V, "d": d, "n_pairs": n, **res,
+                          "buffer_ratio": round(a["accumulate_buffer_bytes"] / b["accumulate_buffer_bytes"], 3),
+                          "note": "the gathered buffer grows with the number of workers (x k after an "
+                                  "all-gather), the dense one does not"}))
         ws.close()
         return
 

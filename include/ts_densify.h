@@ -52,7 +52,8 @@ typedef enum {
     TS_ERR_ALIGN = 3,     /* rows / dense_in / dense_out not 16-byte aligned */
     TS_ERR_WORKSPACE = 4, /* no workspace bound, or it is too small for this call */
     TS_ERR_HIP = 5,       /* the HIP runtime reported an error (launch, event) */
-    TS_ERR_OVERFLOW = 6   /* a size does not fit (n_total >= 2^31, byte count overflow) */
+    TS_ERR_OVERFLOW = 6,  /* a size does not fit (n_total >= 2^31, byte count overflow) */
+    TS_ERR_CAPACITY = 7   /* an output buffer is too small for what the call would write */
 } ts_status;
 
 enum { TS_ROW_FP32 = 0, TS_ROW_BF16 = 1 };
@@ -85,6 +86,48 @@ int ts_densify_bf16(const int32_t* ids, const uint16_t* rows, int64_t n, int32_t
 int ts_densify_multi(const int32_t* const* ids_k, const void* const* rows_k, const int64_t* n_k,
                      int32_t k, int32_t row_dtype, int32_t d, int32_t V,
                      const float* dense_in, float* dense_out, void* stream);
+
+/*
+ * The two accumulation rules of the paper, for the gradients that one variable receives.
+ *
+ * Section 3, Algorithm 1 (TensorFlow's rule, TS_RULE_TF): fewer than two gradients pass
+ * through; if all are dense tensors they are summed (reduce); otherwise all are turned
+ * into indexed slices and concatenated (gather) -- a dense [V, d] tensor becomes V
+ * slices with ids 0 .. V-1.  Section 6, Algorithm 2 (TS_RULE_PROPOSED) adds a branch
+ * before the gather: if any gradient is a dense tensor, all are converted to dense
+ * tensors and summed, which is ts_densify_multi onto the (sum of the) dense one(s).
+ *
+ * ts_accumulate_strategy only tells which branch the rule takes (host logic).
+ * ts_accumulate runs it on `stream`:
+ *   - TS_ACC_REDUCE, TS_ACC_DENSIFY_REDUCE and a passed-through dense gradient write
+ *     dense_out fp32 [V, d] (device; fp32 sums, dense gradients added in list order,
+ *     converted slices as in ts_densify).  TS_ACC_DENSIFY_REDUCE needs the workspace
+ *     bound for the total number of pairs and at most TS_MAX_SHARDS slice gradients.
+ *   - TS_ACC_GATHER and a passed-through slices gradient write ids_out int32 [total]
+ *     and rows_out fp32 [total, d] (device), the gradients' slices in list order, and
+ *     total to *n_slices_out (host); total > slice_capacity gives TS_ERR_CAPACITY
+ *     before anything is written.
+ * Outputs the taken branch does not write may be NULL.  *strategy_out (host, may be
+ * NULL) receives the branch.  grads is a host array of m >= 1 descriptors; value rows
+ * and dense tensors are fp32, 16-byte aligned, and must not overlap the outputs
+ * (except that a single dense gradient may be dense_out itself).
+ */
+typedef struct {
+    int32_t kind;          /* TS_GRAD_DENSE or TS_GRAD_SLICES */
+    int32_t reserved;
+    const int32_t* ids;    /* slices: device int32 [n]; dense: ignored */
+    const float* values;   /* slices: device rows [n, d]; dense: device [V, d] */
+    int64_t n;             /* slices: number of pairs; dense: ignored */
+} ts_grad;
+
+enum { TS_GRAD_DENSE = 0, TS_GRAD_SLICES = 1 };
+enum { TS_RULE_TF = 1, TS_RULE_PROPOSED = 2 };
+enum { TS_ACC_PASS_THROUGH = 0, TS_ACC_REDUCE = 1, TS_ACC_DENSIFY_REDUCE = 2, TS_ACC_GATHER = 3 };
+
+int ts_accumulate_strategy(const ts_grad* grads, int32_t m, int32_t rule, int32_t* strategy_out);
+int ts_accumulate(const ts_grad* grads, int32_t m, int32_t rule, int32_t d, int32_t V,
+                  float* dense_out, int32_t* ids_out, float* rows_out, int64_t slice_capacity,
+                  int64_t* n_slices_out, int32_t* strategy_out, void* stream);
 
 /*
  * Bytes of the two accumulate buffers the paper compares (Section 4, Fig. 5a):

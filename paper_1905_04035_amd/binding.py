@@ -14,13 +14,22 @@ from typing import Optional, Sequence
 import torch
 
 TS_OK = 0
-TS_ERR_NULL, TS_ERR_SHAPE, TS_ERR_ALIGN, TS_ERR_WORKSPACE, TS_ERR_HIP, TS_ERR_OVERFLOW = 1, 2, 3, 4, 5, 6
+TS_ERR_NULL, TS_ERR_SHAPE, TS_ERR_ALIGN, TS_ERR_WORKSPACE, TS_ERR_HIP, TS_ERR_OVERFLOW, TS_ERR_CAPACITY = 1, 2, 3, 4, 5, 6, 7
+TS_GRAD_DENSE, TS_GRAD_SLICES = 0, 1
+TS_RULE_TF, TS_RULE_PROPOSED = 1, 2
+TS_ACC_PASS_THROUGH, TS_ACC_REDUCE, TS_ACC_DENSIFY_REDUCE, TS_ACC_GATHER = 0, 1, 2, 3
 TS_ROW_FP32, TS_ROW_BF16 = 0, 1
 TS_MAX_SHARDS = 64
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libts_densify.so")
 
 _lib = None
+
+
+class TsGrad(C.Structure):
+    """ts_grad of include/ts_densify.h."""
+    _fields_ = [("kind", C.c_int32), ("reserved", C.c_int32), ("ids", C.c_void_p), ("values", C.c_void_p),
+                ("n", C.c_int64)]
 
 
 class TsError(RuntimeError):
@@ -42,6 +51,8 @@ def lib():
         l.ts_densify_bf16.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
         l.ts_densify_multi.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, vp]
         l.ts_buffer_bytes.argtypes = [i64, i64, i32, i32, i32, vp, vp]
+        l.ts_accumulate_strategy.argtypes = [vp, i32, i32, vp]
+        l.ts_accumulate.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, i64, vp, vp, vp]
         l.ts_workspace_bytes.argtypes = [i64, i32, i32, vp]
         l.ts_bind_workspace.argtypes = [vp, i64]
         l.ts_last_views.argtypes = [vp, vp, vp, vp, vp]
@@ -56,6 +67,7 @@ def lib():
         l.ts_status_string.argtypes = [C.c_int]
         l.ts_status_string.restype = C.c_char_p
         for name in ("ts_densify", "ts_densify_bf16", "ts_densify_multi", "ts_buffer_bytes",
+                     "ts_accumulate_strategy", "ts_accumulate",
                      "ts_workspace_bytes", "ts_bind_workspace", "ts_last_views", "ts_unique_ids",
                      "ts_last_launch_info",
                      "ts_profile_begin", "ts_profile_end", "ts_set_piece_tokens", "ts_set_overlap_bytes", "ts_set_sort_part", "ts_set_combine_groups"):
@@ -135,6 +147,41 @@ def ts_densify_multi(ids_k: Sequence[torch.Tensor], rows_k: Sequence[torch.Tenso
     n_arr = (C.c_int64 * max(k, 1))(*[i.numel() for i in ids_k])
     _check(lib().ts_densify_multi(ids_arr, rows_arr, n_arr, k, row_dtype, d, V, _p(dense_in),
                                   _p(dense_out), _stream(stream)), "ts_densify_multi")
+
+
+def _grad_array(grads):
+    """grads: list of ("dense", tensor[V, d]) or ("slices", ids[n], rows[n, d]) -> ts_grad array."""
+    arr = (TsGrad * max(len(grads), 1))()
+    for i, g in enumerate(grads):
+        if g[0] == "dense":
+            t = g[1]
+            assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()
+            arr[i] = TsGrad(TS_GRAD_DENSE, 0, None, t.data_ptr(), 0)
+        else:
+            ids, rows = g[1], g[2]
+            assert ids.is_cuda and ids.dtype == torch.int32 and ids.is_contiguous()
+            assert rows.is_cuda and rows.dtype == torch.float32 and rows.is_contiguous()
+            arr[i] = TsGrad(TS_GRAD_SLICES, 0, ids.data_ptr(), rows.data_ptr(), ids.numel())
+    return arr
+
+
+def ts_accumulate_strategy(grads, rule: int) -> int:
+    st = C.c_int32(-1)
+    _check(lib().ts_accumulate_strategy(_grad_array(grads), len(grads), rule, C.byref(st)),
+           "ts_accumulate_strategy")
+    return st.value
+
+
+def ts_accumulate(grads, rule: int, d: int, V: int, dense_out: Optional[torch.Tensor] = None,
+                  ids_out: Optional[torch.Tensor] = None, rows_out: Optional[torch.Tensor] = None, stream=None):
+    """Returns (strategy, n_slices); n_slices is None when the result is dense."""
+    cap = 0 if ids_out is None else ids_out.numel()
+    if rows_out is not None:
+        assert rows_out.is_cuda and rows_out.dtype == torch.float32 and rows_out.numel() >= cap * d
+    n_out, st = C.c_int64(-1), C.c_int32(-1)
+    _check(lib().ts_accumulate(_grad_array(grads), len(grads), rule, d, V, _p(dense_out), _p(ids_out),
+                               _p(rows_out), cap, C.byref(n_out), C.byref(st), _stream(stream)), "ts_accumulate")
+    return st.value, (n_out.value if n_out.value >= 0 else None)
 
 
 def ts_buffer_bytes(k: int, N: int, d: int, V: int, row_dtype: int = TS_ROW_FP32):

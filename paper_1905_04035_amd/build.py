@@ -1,11 +1,11 @@
-"""Compiles csrc/ts_densify.hip for gfx950 into libts_densify.so next to this file."""
+"""Compiles csrc/*.hip for gfx950 into libts_densify.so next to this file."""
 import os
 import subprocess
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SRC = os.path.join(HERE, "csrc", "ts_densify.hip")
+SRCS = [os.path.join(HERE, "csrc", f) for f in ("ts_densify.hip", "ts_accumulate.hip")]
 LIB = os.path.join(HERE, "libts_densify.so")
 INCLUDE = os.path.join(ROOT, "include")
 
@@ -21,7 +21,7 @@ FLAGS = [
 def build(force: bool = True, verbose: bool = False) -> str:
     if not force and os.path.exists(LIB):
         return LIB
-    cmd = [HIPCC] + FLAGS + ["-o", LIB, SRC]
+    cmd = [HIPCC] + FLAGS + ["-o", LIB] + SRCS
     if verbose:
         print(" ".join(cmd))
     res = subprocess.run(cmd, capture_output=True, text=True)

@@ -1144,6 +1144,7 @@ const char* ts_status_string(int status)
         case TS_ERR_WORKSPACE: return "workspace not bound or too small";
         case TS_ERR_HIP: return "HIP runtime error";
         case TS_ERR_OVERFLOW: return "size overflow";
+        case TS_ERR_CAPACITY: return "output buffer too small";
         default: return "unknown status";
     }
 }

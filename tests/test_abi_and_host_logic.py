@@ -96,6 +96,33 @@ def test_argument_checks_happen_before_any_launch(lib):
     assert lib.ts_last_views(None, None, None, None, None) == ts.TS_ERR_WORKSPACE
 
 
+def test_accumulation_rule_branches_are_host_logic(lib):
+    # Section 3, Algorithm 1 and Section 6, Algorithm 2: the branch depends on the kinds only
+    fake = 0x1000
+
+    def branch(kinds, rule):
+        arr = (ts.TsGrad * len(kinds))()
+        for i, k in enumerate(kinds):
+            arr[i] = ts.TsGrad(k, 0, fake, fake, 5)
+        out = C.c_int32(-1)
+        assert lib.ts_accumulate_strategy(arr, len(kinds), rule, C.byref(out)) == ts.TS_OK
+        return out.value
+
+    D, S = ts.TS_GRAD_DENSE, ts.TS_GRAD_SLICES
+    for rule in (ts.TS_RULE_TF, ts.TS_RULE_PROPOSED):
+        assert branch([D], rule) == branch([S], rule) == ts.TS_ACC_PASS_THROUGH
+        assert branch([D, D, D], rule) == ts.TS_ACC_REDUCE
+        assert branch([S, S], rule) == ts.TS_ACC_GATHER
+    assert branch([S, S, D], ts.TS_RULE_TF) == ts.TS_ACC_GATHER
+    assert branch([S, S, D], ts.TS_RULE_PROPOSED) == ts.TS_ACC_DENSIFY_REDUCE
+    assert branch([D, S], ts.TS_RULE_PROPOSED) == ts.TS_ACC_DENSIFY_REDUCE
+    arr = (ts.TsGrad * 1)(ts.TsGrad(5, 0, fake, fake, 1))
+    out = C.c_int32(-1)
+    assert lib.ts_accumulate_strategy(arr, 1, ts.TS_RULE_TF, C.byref(out)) == ts.TS_ERR_SHAPE
+    assert lib.ts_accumulate_strategy(arr, 0, ts.TS_RULE_TF, C.byref(out)) == ts.TS_ERR_SHAPE
+    assert lib.ts_accumulate_strategy(None, 1, ts.TS_RULE_TF, C.byref(out)) == ts.TS_ERR_NULL
+
+
 def test_tuning_setters_validate(lib):
     assert lib.ts_set_piece_tokens(7) == ts.TS_ERR_SHAPE
     assert lib.ts_set_piece_tokens(0) == ts.TS_OK
@@ -108,8 +135,8 @@ def test_tuning_setters_validate(lib):
 
 
 def test_status_strings(lib):
-    seen = {ts.status_string(i) for i in range(7)}
-    assert len(seen) == 7 and "ok" in seen
+    seen = {ts.status_string(i) for i in range(8)}
+    assert len(seen) == 8 and "ok" in seen
     assert "unknown" in ts.status_string(99)
 
 
