@@ -6,17 +6,19 @@
 //
 //     dense_out[v,:] = dense_in[v,:] + sum_{t : ids[t] == v} rows[t,:]
 //
-// Three kernels per call, all on the caller's stream, no host synchronisation:
+// Three launches per call (four when the pairs need more than one sort slice), all on the
+// caller's stream, no host synchronisation, no allocation:
 //
-//   sort_kernel     stable counting sort of the pairs by id.  Work-group (g, s) owns
-//                   1024 consecutive ids and slice s of the pairs; its 16 wavefronts
-//                   count their sub-slices into LDS-private tables, an exclusive scan
-//                   turns the counts into offsets, and a second walk over the same
-//                   sub-slices hands every owned pair its final position.  A part's
-//                   first position is the number of pairs with a smaller id, which the
-//                   work-group counts itself while it scans, so parts never wait for
-//                   one another.  With one slice this is a single launch; with more,
-//                   a counting launch fills a [slice][id] table first.
+//   sort_kernel     stable counting sort of the pairs by id.  Work-group (g, s) owns `part`
+//                   consecutive ids (128 .. 1024) and slice s of the pairs; its 16
+//                   wavefronts load their sub-slices into registers, count owned pairs
+//                   into LDS-private tables, an exclusive scan turns the counts into
+//                   offsets, and a second walk hands every owned pair its final position.
+//                   A part's first position is the number of pairs with a smaller id,
+//                   which the work-group counts itself while it scans, so parts never
+//                   wait for one another.  With one slice (up to 16384 pairs) this is a
+//                   single launch; with more, a counting launch fills a [slice][id]
+//                   table first.  The sort leaves one 32-byte record per sorted pair.
 //   reduce_kernel   the HBM-bound kernel.  Wavefront items come in two kinds, heavy
 //                   first: (piece of C sorted positions, block of 256 columns), which
 //                   adds the value rows of every output row that starts in the piece
@@ -27,6 +29,13 @@
 //   combine_kernel  for every cut row: partials added in piece order by 16 wavefronts
 //                   (contiguous shares, then the shares in order), dense_in added
 //                   last, result written to dense_out.
+//
+// The sort and the combine are chains of memory latencies that move almost nothing, so
+// their launches also carry work-groups that copy dense rows and keep HBM busy: beside a
+// single-slice sort, rows [0, X) are copied before it is known which of them receive
+// pairs (the reduce and combine kernels, which run later, overwrite those); beside the
+// combine, the untouched rows of [T, V).  The reduce kernel copies the untouched rows of
+// [X, T).
 //
 // No floating-point atomics anywhere: the position of every pair, the cut points and
 // the order of every addition depend on the ids alone, so results are reproducible
