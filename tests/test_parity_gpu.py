@@ -269,3 +269,25 @@ def test_error_codes_from_the_host_checks():
         torch.cuda.synchronize()
     finally:
         ws.close()
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes_and_options(seed):
+    """Seeded random draws of V, d, shard lengths, skew, row type, dense operand and placement."""
+    rng = np.random.default_rng(1000 + seed)
+    V = int(rng.choice([1, 2, 63, 64, 65, 127, 500, 1023, 1024, 1025, 4097, 20000]))
+    d = int(rng.choice([4, 8, 12, 60, 64, 252, 256, 260, 512, 1028]))
+    k = int(rng.integers(1, 6))
+    scale = int(rng.choice([0, 1, 10, 100, 1000, 20000]))
+    n_list = [int(x) for x in rng.integers(0, scale + 1, size=k)]
+    row_dtype = wl.ROW_BF16 if seed % 3 == 0 else wl.ROW_FP32
+    kind = ["zipf", "uniform", "single", "zipf"][seed % 4]
+    exact = seed % 2 == 0
+    w = wl.make_custom(V=V, d=d, n_list=n_list, ids=kind, zipf_s=float(rng.choice([1.05, 1.3, 2.0])),
+                       seed=2000 + seed, row_dtype=row_dtype, integer_values=exact)
+    if seed % 5 == 0 and w.n_total:
+        bad = rng.integers(0, len(w.ids[0]) + 1, size=3)
+        for b in bad[bad < len(w.ids[0])]:
+            w.ids[0][b] = V + int(rng.integers(0, 5))
+    mode = "multi" if (k > 1 or seed % 2) else "single"
+    _case(w, mode=mode, dense=(seed % 7 != 0), in_place=(seed % 6 == 1), exact_bits=exact)
