@@ -842,11 +842,14 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     // rows copied by the sort launches: about as many bytes as HBM moves while a sort runs
     // (a multi-slice sort keeps the whole GPU busy by itself, and with that many pairs a large
     // share of the rows copied blindly would be overwritten: no blind copy then)
-    const int64_t budget = g_overlap_sort >= 0 ? g_overlap_sort : (pl.S == 1 ? kOverlapSortBytes : 0);
+    // (defaults: in proportion to the pairs, because the sort and the combine take that much
+    // less time with fewer of them)
+    const int64_t sixteenths = n >= kFusedSortMax ? 16 : (n * 16 / kFusedSortMax < 2 ? 2 : n * 16 / kFusedSortMax);
+    const int64_t budget = g_overlap_sort >= 0 ? g_overlap_sort : (pl.S == 1 ? kOverlapSortBytes * sixteenths / 16 : 0);
     int64_t rows_per_launch = in_place ? 0 : budget / ((int64_t)8 * d);
     rows_per_launch = rows_per_launch / (kBigCopyRows * kSortWaves) * (kBigCopyRows * kSortWaves);
     // rows copied by the combine launch, taken from the end
-    const int64_t budget_c = g_overlap_combine >= 0 ? g_overlap_combine : kOverlapCombineBytes;
+    const int64_t budget_c = g_overlap_combine >= 0 ? g_overlap_combine : kOverlapCombineBytes * sixteenths / 16;
     int64_t rows_tail = (in_place || pl.NB == 0) ? 0 : budget_c / ((int64_t)8 * d);
     rows_tail = rows_tail / (kBigCopyRows * kSortWaves) * (kBigCopyRows * kSortWaves);
     if (rows_tail > V) rows_tail = V;
