@@ -78,6 +78,8 @@ constexpr int kFusedSortMax = 16384;   // up to here one launch sorts everything
 constexpr int kPieceSmallMax = 32768;  // up to here pieces of 16 positions, above 32
 constexpr int64_t kOverlapSortBytes = 96ll << 20;      // about what HBM moves while a sort launch runs
 constexpr int64_t kOverlapCombineBytes = 40ll << 20;   // same for the combine launch
+constexpr int kOneLevelPieces = 1024;  // up to this many pieces the combine is one launch
+constexpr int kSegmentPieces = 256;    // beyond: segments of this many pieces, then a second launch
 constexpr int kCombineGroups = 32;     // work-groups per column block in the combine kernel
 
 // ------------------------------------------------------------------ device helpers
@@ -245,7 +247,7 @@ struct SortParams {
     uint32_t* bad;      // [S]             pairs of the slice with an id outside [0, V)
     int32_t* n_valid;
     int32_t* n_bad;
-    int32_t* n_cut;     // length of the list of cut rows, cleared here for the reduce kernel
+    int32_t* n_cut;     // lengths of the two lists of cut rows ([0], [1]), cleared here for the reduce kernel
     // Work-groups past the sorting ones copy dense rows [copy_row0, copy_row1) to the output
     // without knowing yet which rows receive pairs (the reduce kernel, which runs after,
     // overwrites those).  It keeps HBM busy while the latency-bound sort runs.
@@ -406,7 +408,8 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
         }
         if (g == 0 && tid == 0) {
             *p.n_bad = (int32_t)nbad;
-            *p.n_cut = 0;
+            p.n_cut[0] = 0;
+            p.n_cut[1] = 0;
         }
     }
 
@@ -503,8 +506,10 @@ struct ReduceParams {
     const float* dense_in;
     float* dense_out;
     float* partial;             // [2 * pieces][d]
-    int32_t* n_cut;             // number of cut rows found so far
-    int4* cut_list;             // (row id, first piece, pieces, -) of every cut row, in no particular order
+    int32_t SEG;                // pieces per segment of a cut row (the combine works segment by segment)
+    int32_t* n_cut;             // [0] segments listed so far, [1] rows of more than one segment
+    int4* cut_list;             // (row id, first piece of the segment, row_start, count), no particular order
+    int4* cut_list2;            // (row id, first piece of the row, row_start, count) of rows of several segments
 };
 
 // NV: 16-byte fp32 vectors per lane (a wavefront item covers 256 * NV columns); BATCH: sorted
@@ -559,10 +564,21 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
     const uint64_t Lm = ballot64(last);
     const uint64_t W = ballot64(whole);
     if (A == 0) return;
-    // a cut row is announced once, by the item that holds its first pair
-    if (cb == 0 && active && !whole && wpos == s) {
-        const int e = atomicAdd(p.n_cut, 1);
-        p.cut_list[e] = make_int4(id, k, (s + c - 1) / C - k + 1, 0);
+    // A cut row is announced segment by segment (SEG pieces each), by the item that holds the
+    // segment's first piece: the lane of the row's first pair, or lane 0 for a later segment.
+    // A row of several segments is also put on the second list, once.
+    if (cb == 0 && active && !whole) {
+        const int k0 = s / C;
+        const bool row_first = wpos == s;
+        const bool seg_first = lane == 0 && s < pos0 && ((k - k0) % p.SEG) == 0;
+        if (row_first || seg_first) {
+            const int e = atomicAdd(&p.n_cut[0], 1);
+            p.cut_list[e] = make_int4(id, k, s, c);
+        }
+        if (row_first && (s + c - 1) / C - k0 + 1 > p.SEG) {
+            const int e = atomicAdd(&p.n_cut[1], 1);
+            p.cut_list2[e] = make_int4(id, k0, s, c);
+        }
     }
     const int a = __builtin_ctzll(A);
     const int b = 64 - __builtin_clzll(A);
@@ -628,18 +644,24 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
 struct CombineParams {
     int32_t V, d, C, ncb;
     const int32_t* count;
-    const int32_t* n_cut;
+    int32_t SEG;                // pieces per segment
+    int32_t level;              // 1: add the pieces of a segment; 2: add the segment sums of a row
+    const int32_t* n_cut;       // the list's length
     const int4* cut_list;
     const float* dense_in;
     float* dense_out;
-    const float* partial;
+    float* partial;
     int32_t groups;             // combining work-groups per column block
     int32_t copy_row0, copy_row1;   // untouched rows copied by the work-groups past the combining ones
 };
 
-// Work-group (e, cb) finishes column block cb of the cut rows e, e + gridDim.x, ...
-// The P pieces of a row are split into 16 contiguous shares, one per wavefront, each
-// added in piece order; wavefront 0 then adds the shares in order and dense_in last.
+// Work-group (e, cb) handles column block cb of the list entries e, e + groups, ...
+// Level 1: an entry is a segment of at most SEG pieces of a cut row.  Its partial rows are
+// split into 16 contiguous shares, one per wavefront, each added in piece order; wavefront 0
+// then adds the shares in order.  If the row has no other segment, dense_in is added and the
+// row is written; otherwise the segment's sum replaces the partial row of its first piece.
+// Level 2 (only launched when rows can have several segments): an entry is such a row; the
+// same walk over its segment sums, dense_in added last, row written.
 __global__ __launch_bounds__(1024, 8) void combine_kernel(CombineParams p)
 {
     __shared__ f4 share[kSortWaves][64];
@@ -661,10 +683,15 @@ __global__ __launch_bounds__(1024, 8) void combine_kernel(CombineParams p)
 
     for (int e = e0; e < ncut; e += p.groups) {
         if (e != e0) ent = p.cut_list[e];
-        const int v = ent.x, k = ent.y;
-        const int P = ent.z;                        // pieces of this row, >= 2
+        const int v = ent.x;
+        const int k0 = ent.z / p.C;                                  // the row's first piece
+        const int Prow = (ent.z + ent.w - 1) / p.C - k0 + 1;        // the row's pieces, >= 2
+        const int k = ent.y;                                         // first piece summed here
+        const int stride = p.level == 1 ? 1 : p.SEG;
+        const int P = p.level == 1 ? min(p.SEG, Prow - (k - k0)) : (Prow + p.SEG - 1) / p.SEG;
+        const bool final = p.level == 2 || Prow <= p.SEG;
         f4 dn = (f4)(0.0f);
-        if (w == 0 && colok && p.dense_in) dn = load_f4_stream(p.dense_in + (size_t)v * p.d + col);
+        if (final && w == 0 && colok && p.dense_in) dn = load_f4_stream(p.dense_in + (size_t)v * p.d + col);
         const int per = (P + kSortWaves - 1) / kSortWaves;
         const int j0 = min(P, w * per);
         const int j1 = min(P, j0 + per);
@@ -677,7 +704,8 @@ __global__ __launch_bounds__(1024, 8) void combine_kernel(CombineParams p)
                 const int j = jb + u;
                 x[u] = (f4)(0.0f);
                 if (j < j1 && colok) {
-                    const size_t sl = (j == 0) ? (size_t)(2 * k + 1) : (size_t)(2 * (k + j));
+                    const int kb = k + j * stride;
+                    const size_t sl = (kb == k0) ? (size_t)(2 * kb + 1) : (size_t)(2 * kb);
                     x[u] = load_f4(p.partial + sl * p.d + col);
                 }
             }
@@ -691,7 +719,12 @@ __global__ __launch_bounds__(1024, 8) void combine_kernel(CombineParams p)
             f4 tot = share[0][lane];
             for (int q = 1; q < kSortWaves; ++q)
                 if (q * per < P) tot += share[q][lane];
-            store_f4_stream(p.dense_out + (size_t)v * p.d + col, tot + dn);
+            if (final) {
+                store_f4_stream(p.dense_out + (size_t)v * p.d + col, tot + dn);
+            } else {
+                const size_t sl = (k == k0) ? (size_t)(2 * k + 1) : (size_t)(2 * k);
+                store_f4(p.partial + sl * p.d + col, tot);
+            }
         }
         __syncthreads();
     }
@@ -726,8 +759,8 @@ __global__ __launch_bounds__(1024) void unique_kernel(const int32_t* count, int 
 
 // ------------------------------------------------------------------ host side
 struct Plan {
-    int32_t S, SL, G, part, C, NB, ncb;   // ncb: 256-column blocks of a row
-    size_t off_nvalid, off_nbad, off_ncut, off_cut_list, off_count, off_row_start, off_sorted, off_tot,
+    int32_t S, SL, G, part, C, NB, SEG, ncb;   // ncb: 256-column blocks of a row
+    size_t off_nvalid, off_nbad, off_ncut, off_cut_list, off_cut_list2, off_count, off_row_start, off_sorted, off_tot,
         off_below, off_bad, off_partial, total;
 };
 
@@ -783,6 +816,9 @@ void make_plan(int64_t n, int32_t d, int32_t V, Plan* pl)
     pl->G = (V + part - 1) / part;
     pl->C = piece_tokens_for(n);
     pl->NB = (int32_t)((n + pl->C - 1) / pl->C);
+    // the combine adds a cut row's partial rows in segments; with few pieces one segment holds
+    // any row and a single combine launch does
+    pl->SEG = pl->NB <= kOneLevelPieces ? (pl->NB > 0 ? pl->NB : 1) : kSegmentPieces;
     pl->ncb = (d + kColBlock - 1) / kColBlock;
     size_t o = 0;
     pl->off_nvalid = o;
@@ -790,7 +826,9 @@ void make_plan(int64_t n, int32_t d, int32_t V, Plan* pl)
     pl->off_ncut = o + 8;
     o = 256;
     pl->off_cut_list = o;
-    o = align_up(o + (size_t)pl->NB * 16, 256);
+    o = align_up(o + (size_t)2 * pl->NB * 16, 256);
+    pl->off_cut_list2 = o;
+    o = align_up(o + ((size_t)pl->NB / pl->SEG + 2) * 16, 256);
     pl->off_count = o;
     o = align_up(o + (size_t)V * 4, 256);
     pl->off_row_start = o;
@@ -892,6 +930,8 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     rp.partial = (float*)(ws + pl.off_partial);
     rp.n_cut = sp.n_cut;
     rp.cut_list = (int4*)(ws + pl.off_cut_list);
+    rp.cut_list2 = (int4*)(ws + pl.off_cut_list2);
+    rp.SEG = pl.SEG;
     rp.copy_row0 = copy_done;
     rp.copy_row1 = tail0;
     const int64_t items = (int64_t)rp.n_piece_items + (in_place ? 0 : tail0 - copy_done);
@@ -920,6 +960,8 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
         cp.C = pl.C;
         cp.ncb = pl.ncb;
         cp.count = sp.count;
+        cp.SEG = pl.SEG;
+        cp.level = 1;
         cp.n_cut = sp.n_cut;
         cp.cut_list = rp.cut_list;
         cp.dense_in = dense_in;
@@ -931,6 +973,15 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
         cp.copy_row1 = V;
         const unsigned cgrid = (unsigned)(cp.groups * pl.ncb + (V - tail0 + kBigCopyRows * kSortWaves - 1) / (kBigCopyRows * kSortWaves));
         hipLaunchKernelGGL(combine_kernel, dim3(cgrid), dim3(1024), 0, stream, cp);
+        if (pl.NB > pl.SEG) {
+            // rows of several segments: add their segment sums
+            cp.level = 2;
+            cp.n_cut = sp.n_cut + 1;
+            cp.cut_list = rp.cut_list2;
+            cp.groups = pl.NB / pl.SEG + 1 < 64 ? pl.NB / pl.SEG + 1 : 64;
+            cp.copy_row0 = cp.copy_row1 = V;
+            hipLaunchKernelGGL(combine_kernel, dim3((unsigned)(cp.groups * pl.ncb)), dim3(1024), 0, stream, cp);
+        }
         if (hipGetLastError() != hipSuccess) return TS_ERR_HIP;
     }
     g_last_plan = pl;
