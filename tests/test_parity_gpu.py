@@ -76,6 +76,9 @@ def test_one_row_takes_every_pair_across_slices():
     _case(w, exact_bits=True, mode="multi")
     wf = wl.make_custom(V=3000, d=128, n_list=[25000, 15000], ids="single", seed=23)
     _case(wf, mode="multi")
+    # 300000 pairs on one row: 9375 pieces, 37 segments for the second combine launch
+    wb = wl.make_custom(V=50, d=16, n_list=[300000], ids="single", seed=24, integer_values=True)
+    _case(wb, exact_bits=True)
 
 
 # ------------------------------------------------------------- shapes and edges
