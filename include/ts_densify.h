@@ -204,7 +204,7 @@ int ts_set_piece_tokens(int32_t piece_tokens);
  */
 int ts_set_overlap_bytes(int64_t sort_bytes, int64_t combine_bytes);
 
-/* Tuning.  Ids owned by one sort work-group (64 .. 1024, power of two; 0 = choose from V and n). */
+/* Tuning.  Ids owned by one sort work-group (64 .. 2048, power of two; 0 = choose from V and n). */
 int ts_set_sort_part(int32_t part);
 
 /* Tuning.  Work-groups per column block that finish cut rows in the combine launch (0 = choose). */

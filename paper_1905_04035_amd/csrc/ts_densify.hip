@@ -64,7 +64,7 @@ struct alignas(32) SortedPair {
 };
 static_assert(sizeof(SortedPair) == 32, "two 16-byte accesses per record");
 
-constexpr int kMaxPart = 1024;     // most ids one sort work-group owns (LDS: 16 x part x 4 B)
+constexpr int kMaxPart = 2048;     // most ids one sort work-group owns (LDS: 18 x part x 4 B = 144 KiB)
 constexpr int kMinPart = 128;
 #ifndef TS_BIG_COPY_ROWS
 #define TS_BIG_COPY_ROWS 2
@@ -345,12 +345,6 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
     }
     __syncthreads();
 
-    const bool idt = tid < part;               // this thread speaks for id lo + tid
-    uint32_t mine = 0;
-    if (idt) {
-#pragma unroll
-        for (int ww = 0; ww < kSortWaves; ++ww) mine += cnt[ww * part + tid];
-    }
     below = wave_sum(below);
     bad = wave_sum(bad);
     if (lane == 0) {
@@ -366,69 +360,88 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
     }
 
     const size_t GV = (size_t)p.G * part;
+    uint32_t base = below_wg, nbad = bad_wg;       // first sorted position of the part; bad ids
     if (MODE == SORT_COUNT) {
-        if (idt) p.tot[(size_t)sl * GV + lo + tid] = mine;
         if (tid == 0) {
             p.below[sl * p.G + g] = below_wg;
             if (g == 0) p.bad[sl] = bad_wg;
         }
-        return;
     }
-
-    uint32_t total = mine, pre = 0, base = below_wg, nbad = bad_wg;
     if (MODE == SORT_SCATTER) {
-        total = 0;
         base = 0;
         nbad = 0;
         for (int s2 = 0; s2 < p.S; ++s2) {
-            const uint32_t x = idt ? p.tot[(size_t)s2 * GV + lo + tid] : 0u;
-            total += x;
-            if (s2 < sl) pre += x;
             base += p.below[s2 * p.G + g];
             nbad += p.bad[s2];
         }
     }
+    if (MODE != SORT_COUNT && sl == 0 && g == 0 && tid == 0) {
+        *p.n_bad = (int32_t)nbad;
+        p.n_cut[0] = 0;
+        p.n_cut[1] = 0;
+    }
 
-    // exclusive scan of the per-id totals over the part
-    const uint32_t incl = wave_inclusive_scan(total, lane);
-    if (lane == 63) red[2 * kSortWaves + w] = incl;
-    __syncthreads();
-    uint32_t woff = 0;
-    for (int ww = 0; ww < w; ++ww) woff += red[2 * kSortWaves + ww];
-    const uint32_t rs = base + woff + incl - total;
+    // The ids of the part, 1024 at a time (thread tid speaks for id lo + i): totals over the
+    // wavefronts (and slices), exclusive scan into first positions, running positions per
+    // wavefront; each id's count and first position are kept where the ranking pass reads them.
+    uint32_t* const id_total = cnt + kSortWaves * part;
+    uint32_t* const id_start = id_total + part;
+    uint32_t carry = base;
+    for (int i0 = 0; i0 < part; i0 += 1024) {
+        const int i = i0 + tid;
+        const bool idt = i < part;
+        uint32_t mine = 0;
+        if (idt) {
+#pragma unroll
+            for (int ww = 0; ww < kSortWaves; ++ww) mine += cnt[ww * part + i];
+        }
+        if (MODE == SORT_COUNT) {
+            if (idt) p.tot[(size_t)sl * GV + lo + i] = mine;
+            continue;
+        }
+        uint32_t total = mine, pre = 0;
+        if (MODE == SORT_SCATTER) {
+            total = 0;
+            for (int s2 = 0; s2 < p.S; ++s2) {
+                const uint32_t x = idt ? p.tot[(size_t)s2 * GV + lo + i] : 0u;
+                total += x;
+                if (s2 < sl) pre += x;
+            }
+        }
+        const uint32_t incl = wave_inclusive_scan(total, lane);
+        if (lane == 63) red[2 * kSortWaves + w] = incl;
+        __syncthreads();
+        uint32_t woff = 0, block_total = 0;
+        for (int ww = 0; ww < kSortWaves; ++ww) {
+            const uint32_t x = red[2 * kSortWaves + ww];
+            if (ww < w) woff += x;
+            block_total += x;
+        }
+        const uint32_t rs = carry + woff + incl - total;
+        carry += block_total;
 
-    if (sl == 0) {
-        if ((uint32_t)tid < span) {
-            p.count[lo + tid] = (int32_t)total;
-            p.row_start[lo + tid] = (int32_t)rs;
-            if (lo + tid == p.V - 1) {
+        if (sl == 0 && (uint32_t)i < span) {
+            p.count[lo + i] = (int32_t)total;
+            p.row_start[lo + i] = (int32_t)rs;
+            if (lo + i == p.V - 1) {
                 p.row_start[p.V] = (int32_t)(rs + total);
                 *p.n_valid = (int32_t)(rs + total);
             }
         }
-        if (g == 0 && tid == 0) {
-            *p.n_bad = (int32_t)nbad;
-            p.n_cut[0] = 0;
-            p.n_cut[1] = 0;
-        }
-    }
-
-    // turn the per-wavefront counts into running positions; keep each id's count and first
-    // position where the ranking pass can read them
-    uint32_t* const id_total = cnt + kSortWaves * part;
-    uint32_t* const id_start = id_total + part;
-    if (idt) {
-        id_total[tid] = total;
-        id_start[tid] = rs;
-        uint32_t o = rs + pre;
+        if (idt) {
+            id_total[i] = total;
+            id_start[i] = rs;
+            uint32_t o = rs + pre;
 #pragma unroll
-        for (int ww = 0; ww < kSortWaves; ++ww) {
-            const uint32_t c = cnt[ww * part + tid];
-            cnt[ww * part + tid] = o;
-            o += c;
+            for (int ww = 0; ww < kSortWaves; ++ww) {
+                const uint32_t c = cnt[ww * part + i];
+                cnt[ww * part + i] = o;
+                o += c;
+            }
         }
+        __syncthreads();
     }
-    __syncthreads();
+    if (MODE == SORT_COUNT) return;
 
     // pass 2: same walk; every owned pair takes the next position of its id.  Pairs of one
     // id inside a tile are ranked by lane, tiles are walked in order and wavefronts own
@@ -808,8 +821,9 @@ void make_plan(int64_t n, int32_t d, int32_t V, Plan* pl)
     // ids per sort work-group: smaller parts shorten the sort (fewer owned pairs per tile),
     // but every sorting work-group holds half of a compute unit and slows the copy that
     // runs beside it; about 64 work-groups per slice measured best
-    // (with several slices the scan of every slice by every part dominates: largest parts)
-    int part = kMaxPart;
+    // (with several slices the scan of every slice by every part dominates: the largest parts
+    // that still give every compute unit a work-group)
+    int part = (pl->S > 1 && (int64_t)((V + kMaxPart - 1) / kMaxPart) * pl->S >= 256) ? kMaxPart : 1024;
     while (pl->S == 1 && part > kMinPart && (int64_t)((V + part - 1) / part) < 64) part >>= 1;
     if (g_part_override) part = g_part_override;
     pl->part = part;
@@ -1178,7 +1192,8 @@ int ts_set_overlap_bytes(int64_t sort_bytes, int64_t combine_bytes)
 
 int ts_set_sort_part(int32_t part)
 {
-    if (part != 0 && part != 64 && part != 128 && part != 256 && part != 512 && part != 1024) return TS_ERR_SHAPE;
+    if (part != 0 && part != 64 && part != 128 && part != 256 && part != 512 && part != 1024 && part != 2048)
+        return TS_ERR_SHAPE;
     g_part_override = part;
     return TS_OK;
 }
