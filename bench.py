@@ -29,7 +29,7 @@ HBM_PEAK_GBPS = 8000.0
 # factors a plain copy of known size gives).  Only valid for the kernel source it was taken
 # with: when the source's hash differs, `traffic` is reported as null.
 COUNTED_TRAFFIC = {
-    "source_sha256": "1a7a587c4c15248bd301022200de637b43adbd2295d39a3ecdbc1d2228afdb69",
+    "source_sha256": "e0b3510c67c299b378a24b02f09ab74aadeb59167c15b2c9703b3167e3e47b73",
     "workload": "transformer_big",
     "reduce_kernel_bytes_per_launch": 212.68e6,
 }

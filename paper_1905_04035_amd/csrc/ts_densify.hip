@@ -519,7 +519,7 @@ struct ReduceParams {
     const float* dense_in;
     float* dense_out;
     float* partial;             // [2 * pieces][d]
-    int32_t SEG;                // pieces per segment of a cut row (the combine works segment by segment)
+    int32_t SEG, logC;          // pieces per segment of a cut row (the combine works segment by segment); log2 C
     int32_t* n_cut;             // [0] segments listed so far, [1] rows of more than one segment
     int4* cut_list;             // (row id, first piece of the segment, row_start, count), no particular order
     int4* cut_list2;            // (row id, first piece of the row, row_start, count) of rows of several segments
@@ -581,14 +581,14 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
     // segment's first piece: the lane of the row's first pair, or lane 0 for a later segment.
     // A row of several segments is also put on the second list, once.
     if (cb == 0 && active && !whole) {
-        const int k0 = s / C;
+        const int k0 = s >> p.logC;          // C and SEG are powers of two
         const bool row_first = wpos == s;
-        const bool seg_first = lane == 0 && s < pos0 && ((k - k0) % p.SEG) == 0;
+        const bool seg_first = lane == 0 && s < pos0 && ((k - k0) & (p.SEG - 1)) == 0;
         if (row_first || seg_first) {
             const int e = atomicAdd(&p.n_cut[0], 1);
             p.cut_list[e] = make_int4(id, k, s, c);
         }
-        if (row_first && (s + c - 1) / C - k0 + 1 > p.SEG) {
+        if (row_first && ((s + c - 1) >> p.logC) - k0 + 1 > p.SEG) {
             const int e = atomicAdd(&p.n_cut[1], 1);
             p.cut_list2[e] = make_int4(id, k0, s, c);
         }
@@ -657,7 +657,7 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
 struct CombineParams {
     int32_t V, d, C, ncb;
     const int32_t* count;
-    int32_t SEG;                // pieces per segment
+    int32_t SEG, logSEG, logC;  // pieces per segment; log2 of it and of C
     int32_t level;              // 1: add the pieces of a segment; 2: add the segment sums of a row
     const int32_t* n_cut;       // the list's length
     const int4* cut_list;
@@ -697,11 +697,11 @@ __global__ __launch_bounds__(1024, 8) void combine_kernel(CombineParams p)
     for (int e = e0; e < ncut; e += p.groups) {
         if (e != e0) ent = p.cut_list[e];
         const int v = ent.x;
-        const int k0 = ent.z / p.C;                                  // the row's first piece
-        const int Prow = (ent.z + ent.w - 1) / p.C - k0 + 1;        // the row's pieces, >= 2
+        const int k0 = ent.z >> p.logC;                              // the row's first piece
+        const int Prow = ((ent.z + ent.w - 1) >> p.logC) - k0 + 1;  // the row's pieces, >= 2
         const int k = ent.y;                                         // first piece summed here
         const int stride = p.level == 1 ? 1 : p.SEG;
-        const int P = p.level == 1 ? min(p.SEG, Prow - (k - k0)) : (Prow + p.SEG - 1) / p.SEG;
+        const int P = p.level == 1 ? min(p.SEG, Prow - (k - k0)) : (Prow + p.SEG - 1) >> p.logSEG;
         const bool final = p.level == 2 || Prow <= p.SEG;
         f4 dn = (f4)(0.0f);
         if (final && w == 0 && colok && p.dense_in) dn = load_f4_stream(p.dense_in + (size_t)v * p.d + col);
@@ -832,7 +832,7 @@ void make_plan(int64_t n, int32_t d, int32_t V, Plan* pl)
     pl->NB = (int32_t)((n + pl->C - 1) / pl->C);
     // the combine adds a cut row's partial rows in segments; with few pieces one segment holds
     // any row and a single combine launch does
-    pl->SEG = pl->NB <= kOneLevelPieces ? (pl->NB > 0 ? pl->NB : 1) : kSegmentPieces;
+    pl->SEG = pl->NB <= kOneLevelPieces ? (1 << 30) : kSegmentPieces;     // powers of two
     pl->ncb = (d + kColBlock - 1) / kColBlock;
     size_t o = 0;
     pl->off_nvalid = o;
@@ -946,6 +946,7 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     rp.cut_list = (int4*)(ws + pl.off_cut_list);
     rp.cut_list2 = (int4*)(ws + pl.off_cut_list2);
     rp.SEG = pl.SEG;
+    rp.logC = __builtin_ctz((unsigned)pl.C);
     rp.copy_row0 = copy_done;
     rp.copy_row1 = tail0;
     const int64_t items = (int64_t)rp.n_piece_items + (in_place ? 0 : tail0 - copy_done);
@@ -975,6 +976,8 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
         cp.ncb = pl.ncb;
         cp.count = sp.count;
         cp.SEG = pl.SEG;
+        cp.logSEG = __builtin_ctz((unsigned)pl.SEG);
+        cp.logC = __builtin_ctz((unsigned)pl.C);
         cp.level = 1;
         cp.n_cut = sp.n_cut;
         cp.cut_list = rp.cut_list;
