@@ -87,6 +87,40 @@ int ts_densify_multi(const int32_t* const* ids_k, const void* const* rows_k, con
                      int32_t k, int32_t row_dtype, int32_t d, int32_t V,
                      const float* dense_in, float* dense_out, void* stream);
 
+enum { TS_OUT_FP32 = 0, TS_OUT_BF16 = 1 };
+
+/*
+ * ts_densify_multi with a write-back epilogue, for a result that goes straight into the
+ * buffer a dense reduction will read (Section 4: after the conversion the gradient is
+ * accumulated by reduction; Section 5, runtime settings: the experiments give the
+ * reduction a fusion buffer of 134217728 bytes, the size of a [32768, 1024] fp32 tensor;
+ * Section 1 names reduced precision as the other way to cut the exchange):
+ *
+ *     out[v,:] = cast( scale * (dense_in[v,:] + sum of the value rows with id v) )
+ *
+ * scale is one finite fp32 factor (1/k turns the sum over k workers into their average;
+ * infinite or NaN: TS_ERR_SHAPE).  The sum is formed in fp32 exactly as by
+ * ts_densify_multi, multiplied once in fp32, then stored as fp32 (TS_OUT_FP32) or rounded
+ * to bf16, nearest with ties to even (TS_OUT_BF16: out holds V*d uint16 bit patterns and
+ * half the bytes are written).  Untouched rows are scale * dense_in, rounded the same way.
+ * With TS_OUT_FP32 and scale == 1 the call is ts_densify_multi, bit for bit.
+ * out is a device pointer, 16-byte aligned, e.g. fusion buffer + the offset that
+ * ts_fusion_place returns.  out == dense_in is allowed for TS_OUT_FP32 only (TS_OUT_BF16:
+ * TS_ERR_SHAPE); other overlaps are undefined.  Everything else as for ts_densify_multi.
+ */
+int ts_densify_scaled(const int32_t* const* ids_k, const void* const* rows_k, const int64_t* n_k,
+                      int32_t k, int32_t row_dtype, int32_t d, int32_t V,
+                      const float* dense_in, void* out, int32_t out_dtype, float scale, void* stream);
+
+/*
+ * Host arithmetic, no GPU: where a [V, d] result of out_dtype goes in a fusion buffer of
+ * capacity_bytes of which used_bytes are taken.  *offset_bytes = used_bytes rounded up to
+ * 256; *used_after_bytes = offset + 4*V*d (2*V*d for bf16).  TS_ERR_CAPACITY if that
+ * exceeds the capacity (nothing is written then), TS_ERR_OVERFLOW if a size overflows.
+ */
+int ts_fusion_place(int64_t capacity_bytes, int64_t used_bytes, int32_t d, int32_t V, int32_t out_dtype,
+                    int64_t* offset_bytes, int64_t* used_after_bytes);
+
 /*
  * The two accumulation rules of the paper, for the gradients that one variable receives.
  *

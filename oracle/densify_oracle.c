@@ -33,7 +33,9 @@
  * float64, column-sum / untouched-row / permutation invariants, exact results for
  * all-distinct ids and for small-integer data, exact power-of-two scaling,
  * decomposition into two calls, and the paper's 11.4 GB / 139 MB / 82x figures
- * for the byte-count formulas.
+ * for the byte-count formulas.  The scaled / bf16 finish: torch's CPU float32 ->
+ * bfloat16 conversion, hand-worked ties and a double-rounding case, exact scaling by
+ * powers of two, the average of k equal contributions, small-integer data.
  */
 #include <math.h>
 #include <stdint.h>
@@ -104,6 +106,90 @@ void oracle_finish(const double* acc, double* abs_sum, const int32_t* count, con
                 out[i] = (float)e;
                 if (exact) exact[i] = e;
                 if (abs_sum && dense_in) abs_sum[i] += fabs((double)dense_in[i]);
+            }
+        }
+    }
+}
+
+/*
+ * Rounds a real number to bf16 (1 sign, 8 exponent, 7 fraction bits: the upper half of
+ * an fp32), nearest with ties to even, in ONE step from the float64 value: the multiple
+ * of the format's spacing at that magnitude that lies nearest.  Below 2^-126 the spacing
+ * stays 2^-133 (subnormals); 2^128 and beyond is infinity.
+ */
+uint16_t oracle_bf16_from_double(double e)
+{
+    if (isnan(e)) return 0x7FC0;
+    uint16_t sign = signbit(e) ? 0x8000 : 0;
+    double a = fabs(e);
+    if (a == 0.0) return sign;
+    if (isinf(a)) return (uint16_t)(sign | 0x7F80);
+    int ex;
+    (void)frexp(a, &ex);                    /* a = m * 2^ex with 0.5 <= m < 1 */
+    int eq = ex - 8;                        /* spacing 2^eq leaves 8 significant bits */
+    if (eq < -133) eq = -133;
+    double q = nearbyint(ldexp(a, -eq));    /* default rounding mode: ties to even; 0 <= q <= 256 */
+    if (q == 256.0) {
+        q = 128.0;
+        eq += 1;
+    }
+    if (q < 128.0) return (uint16_t)(sign | (uint16_t)q);     /* subnormal or zero (only when eq == -133) */
+    int field = eq + 7 + 127;               /* value = (q / 128) * 2^(eq + 7) */
+    if (field >= 255) return (uint16_t)(sign | 0x7F80);
+    return (uint16_t)(sign | (field << 7) | ((int)q - 128));
+}
+
+void oracle_bf16_from_double_array(const double* x, int64_t n, uint16_t* out)
+{
+    for (int64_t i = 0; i < n; ++i) out[i] = oracle_bf16_from_double(x[i]);
+}
+
+enum { ORACLE_OUT_FP32 = 0, ORACLE_OUT_BF16 = 1 };
+
+/*
+ * The finish step with a write-back epilogue (a reduction buffer that wants the average
+ * instead of the sum, or a 16-bit copy of it: Section 4 hands the converted gradient to a
+ * dense reduction; Section 1 mentions reduced precision):
+ *
+ *   rows that received pairs:  e = (acc + dense_in) * scale in float64, rounded ONCE to
+ *                              the output type (fp32: C conversion; bf16: the function
+ *                              above);
+ *   other rows:                y = scale * dense_in as an fp32 product (the float64
+ *                              product of two fp32 numbers is exact, so converting it to
+ *                              float is the correctly rounded product); fp32 output is y
+ *                              (a bit copy of dense_in when scale == 1), bf16 output is
+ *                              y rounded to bf16.
+ * exact receives the unrounded value, abs_sum the sum of |terms| times |scale|.
+ * Exactly one of out_f32 / out_bf16 is used, according to out_dtype.
+ */
+void oracle_finish_scaled(const double* acc, double* abs_sum, const int32_t* count, const float* dense_in,
+                          int32_t d, int32_t V, float scale, int32_t out_dtype, float* out_f32,
+                          uint16_t* out_bf16, double* exact)
+{
+    const double sc = (double)scale;
+    for (int32_t v = 0; v < V; ++v) {
+        for (int32_t c = 0; c < d; ++c) {
+            int64_t i = (int64_t)v * d + c;
+            double x = dense_in ? (double)dense_in[i] : 0.0;
+            if (count[v] == 0) {
+                float y = (float)(sc * x);
+                if (out_dtype == ORACLE_OUT_BF16) {
+                    out_bf16[i] = oracle_bf16_from_double((double)y);
+                } else if (scale == 1.0f && dense_in) {
+                    memcpy(&out_f32[i], &dense_in[i], sizeof(float));
+                } else {
+                    out_f32[i] = y;
+                }
+                if (exact) exact[i] = sc * x;
+                if (abs_sum) abs_sum[i] = fabs(sc * x);
+            } else {
+                double e = (acc[i] + x) * sc;
+                if (out_dtype == ORACLE_OUT_BF16)
+                    out_bf16[i] = oracle_bf16_from_double(e);
+                else
+                    out_f32[i] = (float)e;
+                if (exact) exact[i] = e;
+                if (abs_sum) abs_sum[i] = (abs_sum[i] + fabs(x)) * fabs(sc);
             }
         }
     }

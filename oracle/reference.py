@@ -18,6 +18,8 @@ from . import build as _build
 
 ROW_FP32 = 0
 ROW_BF16 = 1
+OUT_FP32 = 0
+OUT_BF16 = 1
 
 _lib = None
 
@@ -41,6 +43,12 @@ def _load():
         lib.oracle_buffer_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
                                             C.c_void_p, C.c_void_p]
         lib.oracle_buffer_bytes.restype = None
+        lib.oracle_bf16_from_double_array.argtypes = [C.c_void_p, C.c_int64, C.c_void_p]
+        lib.oracle_bf16_from_double_array.restype = None
+        lib.oracle_finish_scaled.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                             C.c_int32, C.c_float, C.c_int32, C.c_void_p, C.c_void_p,
+                                             C.c_void_p]
+        lib.oracle_finish_scaled.restype = None
         _lib = lib
     return _lib
 
@@ -51,7 +59,7 @@ def _ptr(a: Optional[np.ndarray]):
 
 @dataclass
 class OracleResult:
-    out: np.ndarray          # float32 [V, d], the float64 sum rounded once
+    out: np.ndarray          # float32 [V, d], the float64 sum rounded once (uint16 bf16 bit patterns for OUT_BF16)
     exact: np.ndarray        # float64 [V, d], the unrounded sum
     abs_sum: np.ndarray      # float64 [V, d], sum of |terms| per element (tolerance scale)
     count: np.ndarray        # int32 [V], pairs received per row
@@ -67,8 +75,12 @@ def _as_rows(rows: np.ndarray, row_dtype: int, d: int) -> np.ndarray:
 
 
 def densify(ids_k: Sequence[np.ndarray], rows_k: Sequence[np.ndarray], d: int, V: int,
-            dense_in: Optional[np.ndarray], row_dtype: int = ROW_FP32) -> OracleResult:
-    """Densify k contributions (k may be 1), taken in list order, and add dense_in."""
+            dense_in: Optional[np.ndarray], row_dtype: int = ROW_FP32, scale: Optional[float] = None,
+            out_dtype: int = OUT_FP32) -> OracleResult:
+    """Densify k contributions (k may be 1), taken in list order, and add dense_in.
+
+    With scale given (or out_dtype = OUT_BF16) the finish step is the one with the
+    write-back epilogue: out = cast(scale * sum)."""
     lib = _load()
     acc = np.zeros((V, d), dtype=np.float64)
     abs_sum = np.zeros((V, d), dtype=np.float64)
@@ -83,11 +95,28 @@ def densify(ids_k: Sequence[np.ndarray], rows_k: Sequence[np.ndarray], d: int, V
     dn = None if dense_in is None else np.ascontiguousarray(dense_in, dtype=np.float32)
     if dn is not None:
         assert dn.shape == (V, d)
-    out = np.empty((V, d), dtype=np.float32)
     exact = np.empty((V, d), dtype=np.float64)
-    lib.oracle_finish(_ptr(acc), _ptr(abs_sum), _ptr(count), _ptr(dn), d, V, _ptr(out), _ptr(exact))
+    if scale is None and out_dtype == OUT_FP32:
+        out = np.empty((V, d), dtype=np.float32)
+        lib.oracle_finish(_ptr(acc), _ptr(abs_sum), _ptr(count), _ptr(dn), d, V, _ptr(out), _ptr(exact))
+    else:
+        sc = np.float32(1.0 if scale is None else scale)
+        assert np.isfinite(sc)
+        out = np.empty((V, d), dtype=np.uint16 if out_dtype == OUT_BF16 else np.float32)
+        lib.oracle_finish_scaled(_ptr(acc), _ptr(abs_sum), _ptr(count), _ptr(dn), d, V, float(sc), out_dtype,
+                                 _ptr(out) if out_dtype == OUT_FP32 else None,
+                                 _ptr(out) if out_dtype == OUT_BF16 else None, _ptr(exact))
     return OracleResult(out=out, exact=exact, abs_sum=abs_sum, count=count,
                         unique_ids=unique_ids(count), n_bad=int(n_bad[0]))
+
+
+def bf16_round(x: np.ndarray) -> np.ndarray:
+    """bf16 bit patterns (uint16) of float64 values, rounded once, ties to even."""
+    lib = _load()
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    out = np.empty(x.shape, dtype=np.uint16)
+    lib.oracle_bf16_from_double_array(_ptr(x), x.size, _ptr(out))
+    return out
 
 
 def unique_ids(count: np.ndarray) -> np.ndarray:

@@ -19,6 +19,7 @@ TS_GRAD_DENSE, TS_GRAD_SLICES = 0, 1
 TS_RULE_TF, TS_RULE_PROPOSED = 1, 2
 TS_ACC_PASS_THROUGH, TS_ACC_REDUCE, TS_ACC_DENSIFY_REDUCE, TS_ACC_GATHER = 0, 1, 2, 3
 TS_ROW_FP32, TS_ROW_BF16 = 0, 1
+TS_OUT_FP32, TS_OUT_BF16 = 0, 1
 TS_MAX_SHARDS = 64
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libts_densify.so")
@@ -50,6 +51,8 @@ def lib():
         l.ts_densify.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
         l.ts_densify_bf16.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
         l.ts_densify_multi.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, vp]
+        l.ts_densify_scaled.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, i32, C.c_float, vp]
+        l.ts_fusion_place.argtypes = [i64, i64, i32, i32, i32, vp, vp]
         l.ts_buffer_bytes.argtypes = [i64, i64, i32, i32, i32, vp, vp]
         l.ts_accumulate_strategy.argtypes = [vp, i32, i32, vp]
         l.ts_accumulate.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, i64, vp, vp, vp]
@@ -67,6 +70,7 @@ def lib():
         l.ts_status_string.argtypes = [C.c_int]
         l.ts_status_string.restype = C.c_char_p
         for name in ("ts_densify", "ts_densify_bf16", "ts_densify_multi", "ts_buffer_bytes",
+                     "ts_densify_scaled", "ts_fusion_place",
                      "ts_accumulate_strategy", "ts_accumulate",
                      "ts_workspace_bytes", "ts_bind_workspace", "ts_last_views", "ts_unique_ids",
                      "ts_last_launch_info",
@@ -147,6 +151,37 @@ def ts_densify_multi(ids_k: Sequence[torch.Tensor], rows_k: Sequence[torch.Tenso
     n_arr = (C.c_int64 * max(k, 1))(*[i.numel() for i in ids_k])
     _check(lib().ts_densify_multi(ids_arr, rows_arr, n_arr, k, row_dtype, d, V, _p(dense_in),
                                   _p(dense_out), _stream(stream)), "ts_densify_multi")
+
+
+def ts_densify_scaled(ids_k: Sequence[torch.Tensor], rows_k: Sequence[torch.Tensor], row_dtype: int,
+                      d: int, V: int, dense_in: Optional[torch.Tensor], out: torch.Tensor, scale: float,
+                      stream=None) -> None:
+    """out: [V, d] float32, or a 2-byte dtype (bfloat16 / int16 / uint16) for bf16 output; it may
+    be a view into a larger buffer (a fusion buffer at the offset ts_fusion_place gives)."""
+    k = len(ids_k)
+    assert k == len(rows_k)
+    for i, r in zip(ids_k, rows_k):
+        assert r.element_size() == (2 if row_dtype == TS_ROW_BF16 else 4)
+        _check_pair(i, r, d, r.dtype)
+    assert out.is_cuda and out.is_contiguous() and out.numel() == V * d
+    assert out.dtype == torch.float32 or out.element_size() == 2
+    out_dtype = TS_OUT_FP32 if out.dtype == torch.float32 else TS_OUT_BF16
+    if dense_in is not None:
+        assert dense_in.is_cuda and dense_in.dtype == torch.float32 and dense_in.is_contiguous()
+        assert tuple(dense_in.shape) == (V, d)
+    ids_arr = (C.c_void_p * max(k, 1))(*[i.data_ptr() for i in ids_k])
+    rows_arr = (C.c_void_p * max(k, 1))(*[r.data_ptr() for r in rows_k])
+    n_arr = (C.c_int64 * max(k, 1))(*[i.numel() for i in ids_k])
+    _check(lib().ts_densify_scaled(ids_arr, rows_arr, n_arr, k, row_dtype, d, V, _p(dense_in), _p(out),
+                                   out_dtype, C.c_float(scale), _stream(stream)), "ts_densify_scaled")
+
+
+def ts_fusion_place(capacity_bytes: int, used_bytes: int, d: int, V: int, out_dtype: int = TS_OUT_FP32):
+    """(offset_bytes, used_after_bytes) of a [V, d] result in a fusion buffer."""
+    off, used = C.c_int64(-1), C.c_int64(-1)
+    _check(lib().ts_fusion_place(capacity_bytes, used_bytes, d, V, out_dtype, C.byref(off), C.byref(used)),
+           "ts_fusion_place")
+    return off.value, used.value
 
 
 def _grad_array(grads):

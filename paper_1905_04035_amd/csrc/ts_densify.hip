@@ -177,11 +177,41 @@ __device__ __forceinline__ void store_f4_stream(float* p, f4 v)
     __builtin_nontemporal_store(v, reinterpret_cast<f4*>(p));
 }
 
+// What happens to a finished output row on its way to memory.  EPI_NONE: stored as it is
+// (untouched rows are bit copies of dense_in).  EPI_SCALE: every element multiplied by one
+// fp32 factor (an average over k contributions is scale = 1/k).  EPI_SCALE_BF16: the same,
+// then rounded to bf16 (nearest, ties to even), which halves the bytes written.
+enum { EPI_NONE = 0, EPI_SCALE = 1, EPI_SCALE_BF16 = 2 };
+
+__device__ __forceinline__ uint32_t bf16_rne(float x)
+{
+    const uint32_t b = __float_as_uint(x);
+    if ((b & 0x7FFFFFFFu) > 0x7F800000u) return (b >> 16) | 0x0040u;      // NaN stays NaN (quiet)
+    return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
+}
+
+// Stores four consecutive output elements starting at element index idx of the output.
+template <int EPI>
+__device__ __forceinline__ void store_out(void* out, size_t idx, f4 v, float scale)
+{
+    if (EPI == EPI_NONE) {
+        store_f4_stream(reinterpret_cast<float*>(out) + idx, v);
+    } else if (EPI == EPI_SCALE) {
+        store_f4_stream(reinterpret_cast<float*>(out) + idx, v * scale);
+    } else {
+        v = v * scale;
+        u2 b;
+        b.x = bf16_rne(v.x) | (bf16_rne(v.y) << 16);
+        b.y = bf16_rne(v.z) | (bf16_rne(v.w) << 16);
+        __builtin_nontemporal_store(b, reinterpret_cast<u2*>(reinterpret_cast<uint16_t*>(out) + idx));
+    }
+}
+
 // One wavefront copies the dense rows v0 .. v0 + R - 1 that lie below vend (with CHECK only
 // those that received no pair): all loads of all rows are issued before the first store.
-template <bool CHECK, int R>
-__device__ __forceinline__ void copy_rows(const float* dense_in, float* dense_out, const int32_t* count,
-                                          int v0, int vend, int d, int lane)
+template <bool CHECK, int R, int EPI>
+__device__ __forceinline__ void copy_rows(const float* dense_in, void* dense_out, const int32_t* count,
+                                          int v0, int vend, int d, int lane, float scale)
 {
     bool go[R];
     bool any = false;
@@ -207,7 +237,7 @@ __device__ __forceinline__ void copy_rows(const float* dense_in, float* dense_ou
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int col = c0 + u * kColBlock + lane * 4;
-                if (go[r] && col < d) store_f4_stream(dense_out + (size_t)(v0 + r) * d + col, x[r][u]);
+                if (go[r] && col < d) store_out<EPI>(dense_out, (size_t)(v0 + r) * d + col, x[r][u], scale);
             }
     }
 }
@@ -252,8 +282,9 @@ struct SortParams {
     // without knowing yet which rows receive pairs (the reduce kernel, which runs after,
     // overwrites those).  It keeps HBM busy while the latency-bound sort runs.
     const float* copy_in;
-    float* copy_out;
+    void* copy_out;
     int32_t copy_row0, copy_row1, d;
+    float scale;
 };
 
 enum { SORT_FUSED = 0, SORT_COUNT = 1, SORT_SCATTER = 2 };
@@ -284,7 +315,7 @@ __device__ __forceinline__ void load_round(const ShardTable& sh, int j0, int j1,
     }
 }
 
-template <int MODE>
+template <int MODE, int EPI>
 __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
 {
     extern __shared__ uint32_t cnt[];          // [kSortWaves][part] counts, then [2][part] per-id totals and starts
@@ -297,7 +328,7 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
     if ((int)blockIdx.x >= nsort) {
         const int cw = (int)blockIdx.x - nsort;
         const int v = p.copy_row0 + (cw * kSortWaves + w) * kBigCopyRows;
-        copy_rows<false, kBigCopyRows>(p.copy_in, p.copy_out, nullptr, v, p.copy_row1, p.d, lane);
+        copy_rows<false, kBigCopyRows, EPI>(p.copy_in, p.copy_out, nullptr, v, p.copy_row1, p.d, lane, p.scale);
         return;
     }
     const int g = (int)blockIdx.x % p.G;
@@ -517,7 +548,8 @@ struct ReduceParams {
     int32_t n;                  // pairs in the call (records beyond n_valid hold nothing)
     const int32_t* n_valid;
     const float* dense_in;
-    float* dense_out;
+    void* dense_out;
+    float scale;
     float* partial;             // [2 * pieces][d]
     int32_t SEG, logC;          // pieces per segment of a cut row (the combine works segment by segment); log2 C
     int32_t* n_cut;             // [0] segments listed so far, [1] rows of more than one segment
@@ -527,7 +559,7 @@ struct ReduceParams {
 
 // NV: 16-byte fp32 vectors per lane (a wavefront item covers 256 * NV columns); BATCH: sorted
 // positions whose rows are loaded together.
-template <typename RowT, int NV, int BATCH>
+template <typename RowT, int NV, int BATCH, int EPI>
 __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
 {
     const int lane = threadIdx.x & 63;
@@ -537,7 +569,7 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
     if (item >= p.n_piece_items) {
         // ---- copy item: one output row, copied if it received no pair
         const int v = p.copy_row0 + item - p.n_piece_items;
-        copy_rows<true, 1>(p.dense_in, p.dense_out, p.count, v, p.copy_row1, p.d, lane);
+        copy_rows<true, 1, EPI>(p.dense_in, p.dense_out, p.count, v, p.copy_row1, p.d, lane, p.scale);
         return;
     }
 
@@ -637,7 +669,7 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
                         if (colok) {
 #pragma unroll
                             for (int q = 0; q < NV; ++q)
-                                store_f4_stream(p.dense_out + (size_t)vj * p.d + col + 4 * q, acc[q] + dn[u][q]);
+                                store_out<EPI>(p.dense_out, (size_t)vj * p.d + col + 4 * q, acc[q] + dn[u][q], p.scale);
                         }
                     } else {
                         const uint32_t sj = bcast(slot, j);
@@ -662,7 +694,8 @@ struct CombineParams {
     const int32_t* n_cut;       // the list's length
     const int4* cut_list;
     const float* dense_in;
-    float* dense_out;
+    void* dense_out;
+    float scale;
     float* partial;
     int32_t groups;             // combining work-groups per column block
     int32_t copy_row0, copy_row1;   // untouched rows copied by the work-groups past the combining ones
@@ -675,6 +708,7 @@ struct CombineParams {
 // row is written; otherwise the segment's sum replaces the partial row of its first piece.
 // Level 2 (only launched when rows can have several segments): an entry is such a row; the
 // same walk over its segment sums, dense_in added last, row written.
+template <int EPI>
 __global__ __launch_bounds__(1024, 8) void combine_kernel(CombineParams p)
 {
     __shared__ f4 share[kSortWaves][64];
@@ -684,7 +718,7 @@ __global__ __launch_bounds__(1024, 8) void combine_kernel(CombineParams p)
     const int ncombine = p.groups * p.ncb;
     if ((int)blockIdx.x >= ncombine) {
         const int v = p.copy_row0 + (((int)blockIdx.x - ncombine) * kSortWaves + w) * kBigCopyRows;
-        copy_rows<true, kBigCopyRows>(p.dense_in, p.dense_out, p.count, v, p.copy_row1, p.d, lane);
+        copy_rows<true, kBigCopyRows, EPI>(p.dense_in, p.dense_out, p.count, v, p.copy_row1, p.d, lane, p.scale);
         return;
     }
     const int cb = (int)blockIdx.x % p.ncb;
@@ -733,7 +767,7 @@ __global__ __launch_bounds__(1024, 8) void combine_kernel(CombineParams p)
             for (int q = 1; q < kSortWaves; ++q)
                 if (q * per < P) tot += share[q][lane];
             if (final) {
-                store_f4_stream(p.dense_out + (size_t)v * p.d + col, tot + dn);
+                store_out<EPI>(p.dense_out, (size_t)v * p.d + col, tot + dn, p.scale);
             } else {
                 const size_t sl = (k == k0) ? (size_t)(2 * k + 1) : (size_t)(2 * k);
                 store_f4(p.partial + sl * p.d + col, tot);
@@ -862,8 +896,40 @@ void make_plan(int64_t n, int32_t d, int32_t V, Plan* pl)
 
 int check_hip(hipError_t e) { return e == hipSuccess ? TS_OK : TS_ERR_HIP; }
 
+// The three kinds of launches, one instantiation per epilogue (the epilogue is a template
+// argument so that the plain path keeps its code).
+template <int EPI>
+void launch_sort_fused(dim3 grid, size_t lds, hipStream_t stream, const SortParams& sp, const ShardTable& sh)
+{
+    hipLaunchKernelGGL((sort_kernel<SORT_FUSED, EPI>), grid, dim3(1024), lds, stream, sp, sh);
+}
+
+template <int EPI>
+void launch_reduce(unsigned grid, bool wide, int32_t row_dtype, hipStream_t stream, const ReduceParams& rp)
+{
+    if (wide)
+        hipLaunchKernelGGL((reduce_kernel<uint16_t, 2, 4, EPI>), dim3(grid), dim3(256), 0, stream, rp);
+    else if (row_dtype == TS_ROW_BF16)
+        hipLaunchKernelGGL((reduce_kernel<uint16_t, 1, 8, EPI>), dim3(grid), dim3(256), 0, stream, rp);
+    else
+        hipLaunchKernelGGL((reduce_kernel<float, 1, 8, EPI>), dim3(grid), dim3(256), 0, stream, rp);
+}
+
+template <int EPI>
+void launch_combine(unsigned grid, hipStream_t stream, const CombineParams& cp)
+{
+    hipLaunchKernelGGL(combine_kernel<EPI>, dim3(grid), dim3(1024), 0, stream, cp);
+}
+
+#define TS_DISPATCH_EPI(epi, fn, ...)                              \
+    do {                                                           \
+        if ((epi) == EPI_NONE) fn<EPI_NONE>(__VA_ARGS__);          \
+        else if ((epi) == EPI_SCALE) fn<EPI_SCALE>(__VA_ARGS__);   \
+        else fn<EPI_SCALE_BF16>(__VA_ARGS__);                      \
+    } while (0)
+
 int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, int32_t V,
-                 const float* dense_in, float* dense_out, void* stream_v)
+                 const float* dense_in, void* dense_out, int epi, float scale, void* stream_v)
 {
     Plan pl;
     make_plan(n, d, V, &pl);
@@ -890,7 +956,11 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     sp.n_bad = (int32_t*)(ws + pl.off_nbad);
     sp.n_cut = (int32_t*)(ws + pl.off_ncut);
 
-    const bool in_place = dense_in == dense_out;
+    // In place, the plain path leaves untouched rows alone.  With an epilogue they still have
+    // to be scaled, by the item that reads them; only the copy made before the pairs are
+    // sorted must go, because the reduce kernel would read scaled values.
+    const bool in_place = (const void*)dense_in == (const void*)dense_out;
+    const bool skip_untouched = in_place && epi == EPI_NONE;
     // rows copied by the sort launches: about as many bytes as HBM moves while a sort runs
     // (a multi-slice sort keeps the whole GPU busy by itself, and with that many pairs a large
     // share of the rows copied blindly would be overwritten: no blind copy then)
@@ -898,11 +968,11 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     // less time with fewer of them)
     const int64_t sixteenths = n >= kFusedSortMax ? 16 : (n * 16 / kFusedSortMax < 2 ? 2 : n * 16 / kFusedSortMax);
     const int64_t budget = g_overlap_sort >= 0 ? g_overlap_sort : (pl.S == 1 ? kOverlapSortBytes * sixteenths / 16 : 0);
-    int64_t rows_per_launch = in_place ? 0 : budget / ((int64_t)8 * d);
+    int64_t rows_per_launch = (in_place || (pl.S > 1 && epi != EPI_NONE)) ? 0 : budget / ((int64_t)8 * d);
     rows_per_launch = rows_per_launch / (kBigCopyRows * kSortWaves) * (kBigCopyRows * kSortWaves);
     // rows copied by the combine launch, taken from the end
     const int64_t budget_c = g_overlap_combine >= 0 ? g_overlap_combine : kOverlapCombineBytes * sixteenths / 16;
-    int64_t rows_tail = (in_place || pl.NB == 0) ? 0 : budget_c / ((int64_t)8 * d);
+    int64_t rows_tail = (skip_untouched || pl.NB == 0) ? 0 : budget_c / ((int64_t)8 * d);
     rows_tail = rows_tail / (kBigCopyRows * kSortWaves) * (kBigCopyRows * kSortWaves);
     if (rows_tail > V) rows_tail = V;
     const int32_t tail0 = (int32_t)(V - rows_tail);
@@ -916,15 +986,16 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     sp.copy_in = dense_in;
     sp.copy_out = dense_out;
     sp.d = d;
+    sp.scale = scale;
     const size_t lds = (size_t)(kSortWaves + 2) * pl.part * sizeof(uint32_t);
     if (pl.S == 1) {
         const dim3 g1 = sort_grid(sp);
-        hipLaunchKernelGGL(sort_kernel<SORT_FUSED>, g1, dim3(1024), lds, stream, sp, sh);
+        TS_DISPATCH_EPI(epi, launch_sort_fused, g1, lds, stream, sp, sh);
     } else {
         const dim3 g1 = sort_grid(sp);
-        hipLaunchKernelGGL(sort_kernel<SORT_COUNT>, g1, dim3(1024), lds, stream, sp, sh);
+        hipLaunchKernelGGL((sort_kernel<SORT_COUNT, EPI_NONE>), g1, dim3(1024), lds, stream, sp, sh);
         const dim3 g2 = sort_grid(sp);
-        hipLaunchKernelGGL(sort_kernel<SORT_SCATTER>, g2, dim3(1024), lds, stream, sp, sh);
+        hipLaunchKernelGGL((sort_kernel<SORT_SCATTER, EPI_NONE>), g2, dim3(1024), lds, stream, sp, sh);
     }
     if (hipGetLastError() != hipSuccess) return TS_ERR_HIP;
 
@@ -941,6 +1012,7 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     rp.n_valid = sp.n_valid;
     rp.dense_in = dense_in;
     rp.dense_out = dense_out;
+    rp.scale = scale;
     rp.partial = (float*)(ws + pl.off_partial);
     rp.n_cut = sp.n_cut;
     rp.cut_list = (int4*)(ws + pl.off_cut_list);
@@ -949,19 +1021,12 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     rp.logC = __builtin_ctz((unsigned)pl.C);
     rp.copy_row0 = copy_done;
     rp.copy_row1 = tail0;
-    const int64_t items = (int64_t)rp.n_piece_items + (in_place ? 0 : tail0 - copy_done);
+    const int64_t items = (int64_t)rp.n_piece_items + (skip_untouched ? 0 : tail0 - copy_done);
     const unsigned rgrid = (unsigned)((items + 3) / 4);
 
     const bool prof = g_prof_used < g_prof_cap;
     if (prof && hipEventRecord(g_ev[2 * g_prof_used], stream) != hipSuccess) return TS_ERR_HIP;
-    if (rgrid > 0) {
-        if (wide)
-            hipLaunchKernelGGL((reduce_kernel<uint16_t, 2, 4>), dim3(rgrid), dim3(256), 0, stream, rp);
-        else if (row_dtype == TS_ROW_BF16)
-            hipLaunchKernelGGL((reduce_kernel<uint16_t, 1, 8>), dim3(rgrid), dim3(256), 0, stream, rp);
-        else
-            hipLaunchKernelGGL((reduce_kernel<float, 1, 8>), dim3(rgrid), dim3(256), 0, stream, rp);
-    }
+    if (rgrid > 0) TS_DISPATCH_EPI(epi, launch_reduce, rgrid, wide, row_dtype, stream, rp);
     if (prof) {
         if (hipEventRecord(g_ev[2 * g_prof_used + 1], stream) != hipSuccess) return TS_ERR_HIP;
         ++g_prof_used;
@@ -983,13 +1048,14 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
         cp.cut_list = rp.cut_list;
         cp.dense_in = dense_in;
         cp.dense_out = dense_out;
+        cp.scale = scale;
         cp.partial = rp.partial;
         const int want = g_combine_groups ? g_combine_groups : (pl.NB <= 1024 ? kCombineGroups : 4 * kCombineGroups);
         cp.groups = pl.NB < want ? pl.NB : want;
         cp.copy_row0 = tail0;
         cp.copy_row1 = V;
         const unsigned cgrid = (unsigned)(cp.groups * pl.ncb + (V - tail0 + kBigCopyRows * kSortWaves - 1) / (kBigCopyRows * kSortWaves));
-        hipLaunchKernelGGL(combine_kernel, dim3(cgrid), dim3(1024), 0, stream, cp);
+        TS_DISPATCH_EPI(epi, launch_combine, cgrid, stream, cp);
         if (pl.NB > pl.SEG) {
             // rows of several segments: add their segment sums
             cp.level = 2;
@@ -997,7 +1063,7 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
             cp.cut_list = rp.cut_list2;
             cp.groups = pl.NB / pl.SEG + 1 < 64 ? pl.NB / pl.SEG + 1 : 64;
             cp.copy_row0 = cp.copy_row1 = V;
-            hipLaunchKernelGGL(combine_kernel, dim3((unsigned)(cp.groups * pl.ncb)), dim3(1024), 0, stream, cp);
+            TS_DISPATCH_EPI(epi, launch_combine, (unsigned)(cp.groups * pl.ncb), stream, cp);
         }
         if (hipGetLastError() != hipSuccess) return TS_ERR_HIP;
     }
@@ -1015,7 +1081,7 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     return TS_OK;
 }
 
-int validate_common(int64_t n_total, int32_t d, int32_t V, const float* dense_in, float* dense_out)
+int validate_common(int64_t n_total, int32_t d, int32_t V, const float* dense_in, const void* dense_out)
 {
     if (!dense_out) return TS_ERR_NULL;
     if (n_total < 0 || V <= 0 || d <= 0 || (d % 4) != 0) return TS_ERR_SHAPE;
@@ -1025,8 +1091,8 @@ int validate_common(int64_t n_total, int32_t d, int32_t V, const float* dense_in
 }
 
 int densify_shards(const int32_t* const* ids_k, const void* const* rows_k, const int64_t* n_k, int32_t k,
-                   int32_t row_dtype, int32_t d, int32_t V, const float* dense_in, float* dense_out,
-                   void* stream)
+                   int32_t row_dtype, int32_t d, int32_t V, const float* dense_in, void* dense_out, int epi,
+                   float scale, void* stream)
 {
     if (k < 1 || k > TS_MAX_SHARDS) return TS_ERR_SHAPE;
     if (row_dtype != TS_ROW_FP32 && row_dtype != TS_ROW_BF16) return TS_ERR_SHAPE;
@@ -1053,7 +1119,7 @@ int densify_shards(const int32_t* const* ids_k, const void* const* rows_k, const
         off += n_k[j];
     }
     for (int j = k; j <= TS_MAX_SHARDS; ++j) sh.off[j] = (int32_t)off;
-    return densify_impl(sh, n_total, row_dtype, d, V, dense_in, dense_out, stream);
+    return densify_impl(sh, n_total, row_dtype, d, V, dense_in, dense_out, epi, scale, stream);
 }
 
 }  // namespace
@@ -1065,21 +1131,51 @@ int ts_densify(const int32_t* ids, const float* rows, int64_t n, int32_t d, int3
                const float* dense_in, float* dense_out, void* stream)
 {
     const void* r = rows;
-    return densify_shards(&ids, &r, &n, 1, TS_ROW_FP32, d, V, dense_in, dense_out, stream);
+    return densify_shards(&ids, &r, &n, 1, TS_ROW_FP32, d, V, dense_in, dense_out, EPI_NONE, 1.0f, stream);
 }
 
 int ts_densify_bf16(const int32_t* ids, const uint16_t* rows, int64_t n, int32_t d, int32_t V,
                     const float* dense_in, float* dense_out, void* stream)
 {
     const void* r = rows;
-    return densify_shards(&ids, &r, &n, 1, TS_ROW_BF16, d, V, dense_in, dense_out, stream);
+    return densify_shards(&ids, &r, &n, 1, TS_ROW_BF16, d, V, dense_in, dense_out, EPI_NONE, 1.0f, stream);
 }
 
 int ts_densify_multi(const int32_t* const* ids_k, const void* const* rows_k, const int64_t* n_k,
                      int32_t k, int32_t row_dtype, int32_t d, int32_t V, const float* dense_in,
                      float* dense_out, void* stream)
 {
-    return densify_shards(ids_k, rows_k, n_k, k, row_dtype, d, V, dense_in, dense_out, stream);
+    return densify_shards(ids_k, rows_k, n_k, k, row_dtype, d, V, dense_in, dense_out, EPI_NONE, 1.0f, stream);
+}
+
+int ts_densify_scaled(const int32_t* const* ids_k, const void* const* rows_k, const int64_t* n_k,
+                      int32_t k, int32_t row_dtype, int32_t d, int32_t V, const float* dense_in,
+                      void* out, int32_t out_dtype, float scale, void* stream)
+{
+    if (out_dtype != TS_OUT_FP32 && out_dtype != TS_OUT_BF16) return TS_ERR_SHAPE;
+    if (!(scale - scale == 0.0f)) return TS_ERR_SHAPE;                  // infinite or NaN
+    if (out_dtype == TS_OUT_BF16 && out && (const void*)dense_in == out) return TS_ERR_SHAPE;
+    const int epi = out_dtype == TS_OUT_BF16 ? EPI_SCALE_BF16 : (scale == 1.0f ? EPI_NONE : EPI_SCALE);
+    return densify_shards(ids_k, rows_k, n_k, k, row_dtype, d, V, dense_in, out, epi, scale, stream);
+}
+
+int ts_fusion_place(int64_t capacity_bytes, int64_t used_bytes, int32_t d, int32_t V, int32_t out_dtype,
+                    int64_t* offset_bytes, int64_t* used_after_bytes)
+{
+    if (!offset_bytes || !used_after_bytes) return TS_ERR_NULL;
+    if (capacity_bytes < 0 || used_bytes < 0 || d <= 0 || V <= 0) return TS_ERR_SHAPE;
+    if (out_dtype != TS_OUT_FP32 && out_dtype != TS_OUT_BF16) return TS_ERR_SHAPE;
+    int64_t bytes, start, end;
+    if (__builtin_mul_overflow((int64_t)V, (int64_t)d, &bytes) ||
+        __builtin_mul_overflow(bytes, (int64_t)(out_dtype == TS_OUT_BF16 ? 2 : 4), &bytes) ||
+        __builtin_add_overflow(used_bytes, (int64_t)255, &start))
+        return TS_ERR_OVERFLOW;
+    start = start / 256 * 256;
+    if (__builtin_add_overflow(start, bytes, &end)) return TS_ERR_OVERFLOW;
+    if (end > capacity_bytes) return TS_ERR_CAPACITY;
+    *offset_bytes = start;
+    *used_after_bytes = end;
+    return TS_OK;
 }
 
 int ts_buffer_bytes(int64_t k, int64_t N, int32_t d, int32_t V, int32_t row_dtype, int64_t* gathered_bytes,

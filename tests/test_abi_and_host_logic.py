@@ -123,6 +123,39 @@ def test_accumulation_rule_branches_are_host_logic(lib):
     assert lib.ts_accumulate_strategy(None, 1, ts.TS_RULE_TF, C.byref(out)) == ts.TS_ERR_NULL
 
 
+def test_scaled_entry_point_checks_and_fusion_placement(lib):
+    ts.ts_bind_workspace(None)
+    fake = 0x1000
+    ids = (C.c_void_p * 1)(fake)
+    n = (C.c_int64 * 1)(4)
+    f = lambda out, dt, scale, dn=None: lib.ts_densify_scaled(ids, ids, n, 1, 0, 8, 16, dn, out, dt, C.c_float(scale), None)
+    assert f(fake, 2, 1.0) == ts.TS_ERR_SHAPE                       # unknown output type
+    assert f(fake, ts.TS_OUT_FP32, float("inf")) == ts.TS_ERR_SHAPE
+    assert f(fake, ts.TS_OUT_FP32, float("nan")) == ts.TS_ERR_SHAPE
+    assert f(fake, ts.TS_OUT_BF16, 1.0, fake) == ts.TS_ERR_SHAPE    # bf16 output cannot alias dense_in
+    assert f(None, ts.TS_OUT_BF16, 1.0) == ts.TS_ERR_NULL
+    assert f(fake + 8, ts.TS_OUT_BF16, 0.5) == ts.TS_ERR_ALIGN
+    assert f(fake, ts.TS_OUT_BF16, 0.5) == ts.TS_ERR_WORKSPACE      # passes every check, nothing bound
+    assert f(fake, ts.TS_OUT_FP32, 0.5, fake) == ts.TS_ERR_WORKSPACE
+    # Section 5, runtime settings: a fusion buffer of 134217728 bytes holds exactly one
+    # [32768, 1024] fp32 gradient, or two bf16 ones
+    cap = 134217728
+    assert ts.ts_fusion_place(cap, 0, 1024, 32768, ts.TS_OUT_FP32) == (0, cap)
+    off, used = ts.ts_fusion_place(cap, 0, 1024, 32768, ts.TS_OUT_BF16)
+    assert (off, used) == (0, cap // 2)
+    assert ts.ts_fusion_place(cap, used, 1024, 32768, ts.TS_OUT_BF16) == (cap // 2, cap)
+    assert ts.ts_fusion_place(10000, 1, 4, 8, ts.TS_OUT_FP32) == (256, 256 + 128)
+    assert ts.ts_fusion_place(10000, 256, 4, 8, ts.TS_OUT_BF16) == (256, 256 + 64)
+    o, u = C.c_int64(-7), C.c_int64(-7)
+    assert lib.ts_fusion_place(cap, 1, 1024, 32768, 0, C.byref(o), C.byref(u)) == ts.TS_ERR_CAPACITY
+    assert (o.value, u.value) == (-7, -7)
+    assert lib.ts_fusion_place(cap, 0, 1024, 32768, 5, C.byref(o), C.byref(u)) == ts.TS_ERR_SHAPE
+    assert lib.ts_fusion_place(-1, 0, 4, 8, 0, C.byref(o), C.byref(u)) == ts.TS_ERR_SHAPE
+    assert lib.ts_fusion_place(cap, 0, 4, 8, 0, None, C.byref(u)) == ts.TS_ERR_NULL
+    assert lib.ts_fusion_place(2 ** 62, 2 ** 63 - 100, 4, 8, 0, C.byref(o), C.byref(u)) == ts.TS_ERR_OVERFLOW
+    assert lib.ts_fusion_place(2 ** 62, 0, 2 ** 31 - 1, 2 ** 31 - 1, 0, C.byref(o), C.byref(u)) == ts.TS_ERR_OVERFLOW
+
+
 def test_tuning_setters_validate(lib):
     assert lib.ts_set_piece_tokens(7) == ts.TS_ERR_SHAPE
     assert lib.ts_set_piece_tokens(0) == ts.TS_OK
