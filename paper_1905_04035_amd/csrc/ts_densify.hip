@@ -64,7 +64,7 @@ struct alignas(32) SortedPair {
 };
 static_assert(sizeof(SortedPair) == 32, "two 16-byte accesses per record");
 
-constexpr int kMaxPart = 2048;     // most ids one sort work-group owns (LDS: 18 x part x 4 B = 144 KiB)
+constexpr int kMaxPart = 2048;     // most ids one sort work-group owns (LDS: 18 x part x 4 B + 8 KiB of lists = 152 KiB)
 constexpr int kMinPart = 128;
 #ifndef TS_BIG_COPY_ROWS
 #define TS_BIG_COPY_ROWS 2
@@ -76,8 +76,8 @@ constexpr int kMaxSlices = 64;
 constexpr int kSliceTokens = 16384;
 constexpr int kFusedSortMax = 16384;   // up to here one launch sorts everything
 constexpr int kPieceSmallMax = 32768;  // up to here pieces of 16 positions, above 32
-constexpr int64_t kOverlapSortBytes = 96ll << 20;      // about what HBM moves while a sort launch runs
-constexpr int64_t kOverlapCombineBytes = 40ll << 20;   // same for the combine launch
+constexpr int64_t kOverlapSortBytes = 48ll << 20;      // about what HBM moves while a sort launch runs
+constexpr int64_t kOverlapCombineBytes = 32ll << 20;   // same for the combine launch
 constexpr int kOneLevelPieces = 1024;  // up to this many pieces the combine is one launch
 constexpr int kSegmentPieces = 256;    // beyond: segments of this many pieces, then a second launch
 constexpr int kCombineGroups = 32;     // work-groups per column block in the combine kernel
@@ -237,7 +237,14 @@ __device__ __forceinline__ void copy_rows(const float* dense_in, void* dense_out
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int col = c0 + u * kColBlock + lane * 4;
-                if (go[r] && col < d) store_out<EPI>(dense_out, (size_t)(v0 + r) * d + col, x[r][u], scale);
+                if (go[r] && col < d) {
+                    // (the plain path spelled out: routing it through store_out changes the code
+                    // the compiler makes for it, and that code measured slower)
+                    if constexpr (EPI == EPI_NONE)
+                        store_f4_stream(reinterpret_cast<float*>(dense_out) + (size_t)(v0 + r) * d + col, x[r][u]);
+                    else
+                        store_out<EPI>(dense_out, (size_t)(v0 + r) * d + col, x[r][u], scale);
+                }
             }
     }
 }
@@ -268,6 +275,7 @@ __device__ __forceinline__ void locate(const ShardTable& sh, int j0, int j1, int
 struct SortParams {
     int32_t n, V, G, S, SL;
     int32_t part;       // ids owned by one work-group (power of two)
+    int32_t list_cap;   // entries in a wavefront's list of owned pairs (a multiple of 64, at least 128)
     int32_t row_bytes;
     int32_t* count;
     int32_t* row_start;
@@ -315,10 +323,56 @@ __device__ __forceinline__ void load_round(const ShardTable& sh, int j0, int j1,
     }
 }
 
+// Walks the tiles of a round and appends the pairs that this work-group owns to the
+// wavefront's list, in input order (tiles in order, lanes in order).  An entry is
+// (id - lo) << 10 | position of the pair in the round.  Every work-group looks at every
+// pair of its slice but owns few of them: counting and ranking walk the short list.
+// The list holds cap entries (a whole round when LDS allows, kListCap otherwise); when the
+// next tile might not fit, flush(list, count) consumes what is listed and the list starts
+// again (flushed tells the caller that the list no longer holds the whole round).  Returns
+// the entries left in the list.
+// With TALLY the pairs with a valid id below the part and those with an id outside [0, V)
+// are counted as well (wave-uniform counts).
+constexpr int kListCap = 128;
+
+template <bool TALLY, typename Flush>
+__device__ __forceinline__ uint32_t own_pairs(const int32_t (&idr)[kRoundTiles], int a0, int b, int lane, int lo,
+                                              uint32_t span, uint32_t V, uint32_t* list, uint32_t cap,
+                                              uint32_t& below, uint32_t& bad, bool& flushed, Flush&& flush)
+{
+    uint32_t nown = 0;
+#pragma unroll
+    for (int u = 0; u < kRoundTiles; ++u) {
+        if (a0 + u * 64 < b) {
+            const bool valid = a0 + u * 64 + lane < b;
+            const uint32_t id = (uint32_t)idr[u];
+            const uint32_t rel = id - (uint32_t)lo;
+            const bool own = valid && rel < span;
+            const uint64_t m = ballot64(own);
+            if (TALLY) {
+                below += (uint32_t)__popcll(ballot64(valid && id < (uint32_t)lo));
+                bad += (uint32_t)__popcll(ballot64(valid && id >= V));
+            }
+            if (m) {
+                if (nown > cap - 64u) {
+                    flush(list, nown);
+                    nown = 0;
+                    flushed = true;
+                }
+                if (own) list[nown + lanes_below(m)] = (rel << 10) | (uint32_t)(u * 64 + lane);
+                nown += (uint32_t)__popcll(m);
+            }
+        }
+    }
+    return nown;
+}
+
 template <int MODE, int EPI>
 __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
 {
-    extern __shared__ uint32_t cnt[];          // [kSortWaves][part] counts, then [2][part] per-id totals and starts
+    // [kSortWaves][part] counts, then [2][part] per-id totals and starts, then
+    // [kSortWaves][list_cap] lists of owned pairs
+    extern __shared__ uint32_t cnt[];
     __shared__ uint32_t red[3 * kSortWaves];
 
     const int tid = threadIdx.x;
@@ -337,6 +391,9 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
     const int lo = g * part;
     const uint32_t span = (uint32_t)min(part, p.V - lo);
     uint32_t* const mycnt = cnt + w * part;
+    uint32_t* const id_total = cnt + kSortWaves * part;
+    uint32_t* const id_start = id_total + part;
+    uint32_t* const list = id_start + part + w * p.list_cap;
 
     for (int i = tid; i < kSortWaves * part; i += 1024) cnt[i] = 0u;
 
@@ -359,25 +416,18 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
     if (rounds > 0) load_round(sh, j0, j1, ids0, off0, a, b, lane, idr);
     __syncthreads();
 
-    // pass 1: count owned pairs per (wavefront, id); count what lies below the part
-    uint32_t below = 0, bad = 0;
+    // pass 1: list the owned pairs, count them per (wavefront, id); count what lies below the part
+    uint32_t below = 0, bad = 0, nown = 0;
+    bool flushed = false;
+    auto count_listed = [&](const uint32_t* l, uint32_t cnt_l) {
+        for (uint32_t t = lane; t < cnt_l; t += 64) atomicAdd(&mycnt[l[t] >> 10], 1u);
+    };
     for (int r = 0; r < rounds; ++r) {
         const int a0 = a + r * kRoundPairs;
         if (r > 0) load_round(sh, j0, j1, ids0, off0, a0, b, lane, idr);
-#pragma unroll
-        for (int u = 0; u < kRoundTiles; ++u) {
-            const bool valid = a0 + u * 64 + lane < b;
-            const int32_t id = idr[u];
-            const uint32_t rel = (uint32_t)(id - lo);
-            if (valid && rel < span) atomicAdd(&mycnt[rel], 1u);
-            below += (valid && id >= 0 && id < lo) ? 1u : 0u;
-            bad += (valid && (id < 0 || id >= p.V)) ? 1u : 0u;
-        }
+        nown = own_pairs<true>(idr, a0, b, lane, lo, span, (uint32_t)p.V, list, (uint32_t)p.list_cap, below, bad, flushed, count_listed);
+        count_listed(list, nown);
     }
-    __syncthreads();
-
-    below = wave_sum(below);
-    bad = wave_sum(bad);
     if (lane == 0) {
         red[w] = below;
         red[kSortWaves + w] = bad;
@@ -399,12 +449,11 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
         }
     }
     if (MODE == SORT_SCATTER) {
-        base = 0;
-        nbad = 0;
-        for (int s2 = 0; s2 < p.S; ++s2) {
-            base += p.below[s2 * p.G + g];
-            nbad += p.bad[s2];
-        }
+        // lane s2 fetches slice s2's figures (at most 64 slices): one memory latency for all
+        const uint32_t bl = lane < p.S ? p.below[lane * p.G + g] : 0u;
+        const uint32_t bd = lane < p.S ? p.bad[lane] : 0u;
+        base = wave_sum(bl);
+        nbad = wave_sum(bd);
     }
     if (MODE != SORT_COUNT && sl == 0 && g == 0 && tid == 0) {
         *p.n_bad = (int32_t)nbad;
@@ -415,8 +464,6 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
     // The ids of the part, 1024 at a time (thread tid speaks for id lo + i): totals over the
     // wavefronts (and slices), exclusive scan into first positions, running positions per
     // wavefront; each id's count and first position are kept where the ranking pass reads them.
-    uint32_t* const id_total = cnt + kSortWaves * part;
-    uint32_t* const id_start = id_total + part;
     uint32_t carry = base;
     for (int i0 = 0; i0 < part; i0 += 1024) {
         const int i = i0 + tid;
@@ -432,11 +479,18 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
         }
         uint32_t total = mine, pre = 0;
         if (MODE == SORT_SCATTER) {
+            // the id's count in every slice, eight loads in flight at a time
             total = 0;
-            for (int s2 = 0; s2 < p.S; ++s2) {
-                const uint32_t x = idt ? p.tot[(size_t)s2 * GV + lo + i] : 0u;
-                total += x;
-                if (s2 < sl) pre += x;
+            for (int sb = 0; sb < p.S; sb += 8) {
+                uint32_t x[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q)
+                    x[q] = (idt && sb + q < p.S) ? p.tot[(size_t)(sb + q) * GV + lo + i] : 0u;
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    total += x[q];
+                    if (sb + q < sl) pre += x[q];
+                }
             }
         }
         const uint32_t incl = wave_inclusive_scan(total, lane);
@@ -474,58 +528,52 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
     }
     if (MODE == SORT_COUNT) return;
 
-    // pass 2: same walk; every owned pair takes the next position of its id.  Pairs of one
-    // id inside a tile are ranked by lane, tiles are walked in order and wavefronts own
-    // consecutive sub-slices, so the sort is stable.  Per tile: one LDS read of the running
-    // positions, a scalar loop over the distinct owned ids, one LDS write by the last lane
-    // of each id.
-    for (int r = 0; r < rounds; ++r) {
-        const int a0 = a + r * kRoundPairs;
-        if (rounds > 1) load_round(sh, j0, j1, ids0, off0, a0, b, lane, idr);
-        // (not unrolled: one copy of the body keeps the kernel within 64 registers; the
-        // wave-uniform index into idr becomes a relative register move)
-#pragma unroll 1
-        for (int u = 0; u < kRoundTiles; ++u) {
-            if (a0 + u * 64 >= b) break;
-            const int idx = a0 + u * 64 + lane;
-            const bool valid = idx < b;
-            const int32_t id = idr[u];
-            const uint32_t rel = (uint32_t)(id - lo);
-            const bool own = valid && rel < span;
+    // pass 2: every owned pair takes the next position of its id.  The list keeps the pairs in
+    // input order and wavefronts own consecutive sub-slices, so the sort is stable.  Per 64
+    // list entries: one LDS read of the running positions, a scalar loop over the distinct
+    // ids among them (pairs of one id are ranked by lane), one LDS write by the last lane of
+    // each id.  With a single round whose owned pairs fitted the list, the list of pass 1 is
+    // still there; otherwise the round is walked again.
+    int a0 = a;
+    auto rank_listed = [&](const uint32_t* l, uint32_t cnt_l) {
+        for (uint32_t e0 = 0; e0 < cnt_l; e0 += 64) {
+            const bool own = e0 + lane < cnt_l;
+            const uint32_t ent = own ? l[e0 + lane] : 0u;
+            const uint32_t rel = ent >> 10;
+            const int idx = a0 + (int)(ent & 1023u);
             uint64_t m = ballot64(own);
-            if (m == 0) continue;
             const uint32_t basev = own ? mycnt[rel] : 0u;
             const uint32_t tot_l = own ? id_total[rel] : 0u;
             const uint32_t rs_l = own ? id_start[rel] : 0u;
             uint32_t pos = 0, next = 0;
             bool leader = false;
             while (m) {
-                const int l = __builtin_ctzll(m);
-                const uint32_t rl = bcast(rel, l);
+                const int ll = __builtin_ctzll(m);
+                const uint32_t rl = bcast(rel, ll);
                 const bool same = own && rel == rl;
                 const uint64_t sm = ballot64(same);
                 if (same) pos = basev + lanes_below(sm);
-                if (lane == l) {
+                if (lane == ll) {
                     leader = true;
                     next = basev + (uint32_t)__popcll(sm);
                 }
                 m &= ~sm;
             }
             if (leader) mycnt[rel] = next;
-            // lanes exchange running positions through LDS from one tile to the next: the
+            // lanes exchange running positions through LDS from one step to the next: the
             // hardware keeps a wavefront's LDS accesses in order, the compiler must too
             asm volatile("" ::: "memory");
             if (own) {
                 uint64_t row_addr = (uint64_t)(uintptr_t)rows0 + (uint64_t)(idx - off0) * (uint64_t)p.row_bytes;
                 if (j0 != j1) {
                     const int32_t* idp = nullptr;
-                    locate(sh, j0, j1, idx, valid, p.row_bytes, idp, row_addr);
+                    locate(sh, j0, j1, idx, true, p.row_bytes, idp, row_addr);
                 }
                 u4* rec = reinterpret_cast<u4*>(p.sorted + pos);
                 u4 r0, r1;
                 r0.x = (uint32_t)row_addr;
                 r0.y = (uint32_t)(row_addr >> 32);
-                r0.z = (uint32_t)id;
+                r0.z = (uint32_t)lo + rel;
                 r0.w = (uint32_t)idx;
                 r1.x = tot_l;
                 r1.y = rs_l;
@@ -535,6 +583,18 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
                 rec[1] = r1;
             }
         }
+    };
+    if (rounds == 1 && !flushed) {
+        rank_listed(list, nown);
+        return;
+    }
+    for (int r = 0; r < rounds; ++r) {
+        a0 = a + r * kRoundPairs;
+        if (rounds > 1) load_round(sh, j0, j1, ids0, off0, a0, b, lane, idr);
+        uint32_t unused0 = 0, unused1 = 0;
+        bool unused2 = false;
+        nown = own_pairs<false>(idr, a0, b, lane, lo, span, (uint32_t)p.V, list, (uint32_t)p.list_cap, unused0, unused1, unused2, rank_listed);
+        rank_listed(list, nown);
     }
 }
 
@@ -669,7 +729,11 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
                         if (colok) {
 #pragma unroll
                             for (int q = 0; q < NV; ++q)
-                                store_out<EPI>(p.dense_out, (size_t)vj * p.d + col + 4 * q, acc[q] + dn[u][q], p.scale);
+                                if constexpr (EPI == EPI_NONE)
+                                    store_f4_stream(reinterpret_cast<float*>(p.dense_out) + (size_t)vj * p.d + col + 4 * q,
+                                                    acc[q] + dn[u][q]);
+                                else
+                                    store_out<EPI>(p.dense_out, (size_t)vj * p.d + col + 4 * q, acc[q] + dn[u][q], p.scale);
                         }
                     } else {
                         const uint32_t sj = bcast(slot, j);
@@ -767,7 +831,10 @@ __global__ __launch_bounds__(1024, 8) void combine_kernel(CombineParams p)
             for (int q = 1; q < kSortWaves; ++q)
                 if (q * per < P) tot += share[q][lane];
             if (final) {
-                store_out<EPI>(p.dense_out, (size_t)v * p.d + col, tot + dn, p.scale);
+                if constexpr (EPI == EPI_NONE)
+                    store_f4_stream(reinterpret_cast<float*>(p.dense_out) + (size_t)v * p.d + col, tot + dn);
+                else
+                    store_out<EPI>(p.dense_out, (size_t)v * p.d + col, tot + dn, p.scale);
             } else {
                 const size_t sl = (k == k0) ? (size_t)(2 * k + 1) : (size_t)(2 * k);
                 store_f4(p.partial + sl * p.d + col, tot);
@@ -964,14 +1031,14 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     // rows copied by the sort launches: about as many bytes as HBM moves while a sort runs
     // (a multi-slice sort keeps the whole GPU busy by itself, and with that many pairs a large
     // share of the rows copied blindly would be overwritten: no blind copy then)
-    // (defaults: in proportion to the pairs, because the sort and the combine take that much
-    // less time with fewer of them)
-    const int64_t sixteenths = n >= kFusedSortMax ? 16 : (n * 16 / kFusedSortMax < 2 ? 2 : n * 16 / kFusedSortMax);
-    const int64_t budget = g_overlap_sort >= 0 ? g_overlap_sort : (pl.S == 1 ? kOverlapSortBytes * sixteenths / 16 : 0);
+    // (defaults: a fixed part plus a part in proportion to the pairs, like the time that the
+    // sort and the combine take)
+    const int64_t sixteenths = n >= kFusedSortMax ? 16 : n * 16 / kFusedSortMax;
+    const int64_t budget = g_overlap_sort >= 0 ? g_overlap_sort : (pl.S == 1 ? kOverlapSortBytes * (32 + sixteenths) / 48 : 0);
     int64_t rows_per_launch = (in_place || (pl.S > 1 && epi != EPI_NONE)) ? 0 : budget / ((int64_t)8 * d);
     rows_per_launch = rows_per_launch / (kBigCopyRows * kSortWaves) * (kBigCopyRows * kSortWaves);
     // rows copied by the combine launch, taken from the end
-    const int64_t budget_c = g_overlap_combine >= 0 ? g_overlap_combine : kOverlapCombineBytes * sixteenths / 16;
+    const int64_t budget_c = g_overlap_combine >= 0 ? g_overlap_combine : kOverlapCombineBytes * (16 + sixteenths) / 32;
     int64_t rows_tail = (skip_untouched || pl.NB == 0) ? 0 : budget_c / ((int64_t)8 * d);
     rows_tail = rows_tail / (kBigCopyRows * kSortWaves) * (kBigCopyRows * kSortWaves);
     if (rows_tail > V) rows_tail = V;
@@ -987,7 +1054,10 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     sp.copy_out = dense_out;
     sp.d = d;
     sp.scale = scale;
-    const size_t lds = (size_t)(kSortWaves + 2) * pl.part * sizeof(uint32_t);
+    // a list that holds a whole round never has to be rebuilt; parts of 2048 ids leave room
+    // for short lists only
+    sp.list_cap = pl.part <= 1024 ? kRoundPairs : kListCap;
+    const size_t lds = ((size_t)(kSortWaves + 2) * pl.part + (size_t)kSortWaves * sp.list_cap) * sizeof(uint32_t);
     if (pl.S == 1) {
         const dim3 g1 = sort_grid(sp);
         TS_DISPATCH_EPI(epi, launch_sort_fused, g1, lds, stream, sp, sh);
