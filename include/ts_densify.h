@@ -113,6 +113,25 @@ int ts_densify_scaled(const int32_t* const* ids_k, const void* const* rows_k, co
                       const float* dense_in, void* out, int32_t out_dtype, float scale, void* stream);
 
 /*
+ * The share of one owner when the vocabulary is split among owners: only rows
+ * [v_begin, v_end) of the [V, d] result are produced (Section 3: under the gather strategy
+ * every worker receives every worker's slices; an owner of a range of rows then needs only
+ * the pairs that name its rows.  Section 6, Algorithm 2: those are converted and summed
+ * onto its slice of the dense gradient).  dense_in (or NULL) and dense_out point to that
+ * slice, [v_end - v_begin, d] fp32; row v of the vocabulary is row v - v_begin of the slice.
+ * Pairs with an id in [0, V) outside the range are skipped without being counted as bad;
+ * ids outside [0, V) are skipped and counted.  After the call ts_last_views describes the
+ * slice: count and row_start have v_end - v_begin (+ 1) entries, n_valid is the number of
+ * pairs inside the range, so n_total - n_valid - n_bad_ids pairs belonged to other owners.
+ * 0 <= v_begin < v_end <= V, else TS_ERR_SHAPE.  The workspace is sized for
+ * ts_workspace_bytes(n_total, d, v_end - v_begin).  Everything else as for
+ * ts_densify_multi, which is the case v_begin = 0, v_end = V.
+ */
+int ts_densify_range(const int32_t* const* ids_k, const void* const* rows_k, const int64_t* n_k,
+                     int32_t k, int32_t row_dtype, int32_t d, int32_t V, int32_t v_begin, int32_t v_end,
+                     const float* dense_in, float* dense_out, void* stream);
+
+/*
  * Host arithmetic, no GPU: where a [V, d] result of out_dtype goes in a fusion buffer of
  * capacity_bytes of which used_bytes are taken.  *offset_bytes = used_bytes rounded up to
  * 256; *used_after_bytes = offset + 4*V*d (2*V*d for bf16).  TS_ERR_CAPACITY if that

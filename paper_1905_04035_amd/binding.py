@@ -53,6 +53,7 @@ def lib():
         l.ts_densify_multi.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, vp]
         l.ts_densify_scaled.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, i32, C.c_float, vp]
         l.ts_fusion_place.argtypes = [i64, i64, i32, i32, i32, vp, vp]
+        l.ts_densify_range.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp]
         l.ts_buffer_bytes.argtypes = [i64, i64, i32, i32, i32, vp, vp]
         l.ts_accumulate_strategy.argtypes = [vp, i32, i32, vp]
         l.ts_accumulate.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, i64, vp, vp, vp]
@@ -70,7 +71,7 @@ def lib():
         l.ts_status_string.argtypes = [C.c_int]
         l.ts_status_string.restype = C.c_char_p
         for name in ("ts_densify", "ts_densify_bf16", "ts_densify_multi", "ts_buffer_bytes",
-                     "ts_densify_scaled", "ts_fusion_place",
+                     "ts_densify_scaled", "ts_fusion_place", "ts_densify_range",
                      "ts_accumulate_strategy", "ts_accumulate",
                      "ts_workspace_bytes", "ts_bind_workspace", "ts_last_views", "ts_unique_ids",
                      "ts_last_launch_info",
@@ -174,6 +175,23 @@ def ts_densify_scaled(ids_k: Sequence[torch.Tensor], rows_k: Sequence[torch.Tens
     n_arr = (C.c_int64 * max(k, 1))(*[i.numel() for i in ids_k])
     _check(lib().ts_densify_scaled(ids_arr, rows_arr, n_arr, k, row_dtype, d, V, _p(dense_in), _p(out),
                                    out_dtype, C.c_float(scale), _stream(stream)), "ts_densify_scaled")
+
+
+def ts_densify_range(ids_k: Sequence[torch.Tensor], rows_k: Sequence[torch.Tensor], row_dtype: int,
+                     d: int, V: int, v_begin: int, v_end: int, dense_in: Optional[torch.Tensor],
+                     dense_out: torch.Tensor, stream=None) -> None:
+    """dense_in / dense_out: the [v_end - v_begin, d] slice of the owner of rows v_begin .. v_end - 1."""
+    k = len(ids_k)
+    assert k == len(rows_k)
+    for i, r in zip(ids_k, rows_k):
+        assert r.element_size() == (2 if row_dtype == TS_ROW_BF16 else 4)
+        _check_pair(i, r, d, r.dtype)
+    _check_dense(d, v_end - v_begin, dense_in, dense_out)
+    ids_arr = (C.c_void_p * max(k, 1))(*[i.data_ptr() for i in ids_k])
+    rows_arr = (C.c_void_p * max(k, 1))(*[r.data_ptr() for r in rows_k])
+    n_arr = (C.c_int64 * max(k, 1))(*[i.numel() for i in ids_k])
+    _check(lib().ts_densify_range(ids_arr, rows_arr, n_arr, k, row_dtype, d, V, v_begin, v_end, _p(dense_in),
+                                  _p(dense_out), _stream(stream)), "ts_densify_range")
 
 
 def ts_fusion_place(capacity_bytes: int, used_bytes: int, d: int, V: int, out_dtype: int = TS_OUT_FP32):

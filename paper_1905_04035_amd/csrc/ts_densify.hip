@@ -274,6 +274,10 @@ __device__ __forceinline__ void locate(const ShardTable& sh, int j0, int j1, int
 // ------------------------------------------------------------------ sort
 struct SortParams {
     int32_t n, V, G, S, SL;
+    // The rows of the call are ids id_base .. id_base + V - 1 of a vocabulary of V_total ids
+    // (the whole vocabulary: id_base = 0, V_total = V).  Ids of the vocabulary outside the
+    // call's range belong to another owner: skipped, but not counted as bad.
+    int32_t id_base, V_total;
     int32_t part;       // ids owned by one work-group (power of two)
     int32_t list_cap;   // entries in a wavefront's list of owned pairs (a multiple of 64, at least 128)
     int32_t row_bytes;
@@ -337,21 +341,23 @@ constexpr int kListCap = 128;
 
 template <bool TALLY, typename Flush>
 __device__ __forceinline__ uint32_t own_pairs(const int32_t (&idr)[kRoundTiles], int a0, int b, int lane, int lo,
-                                              uint32_t span, uint32_t V, uint32_t* list, uint32_t cap,
-                                              uint32_t& below, uint32_t& bad, bool& flushed, Flush&& flush)
+                                              uint32_t span, uint32_t id_base, uint32_t V_total, uint32_t* list,
+                                              uint32_t cap, uint32_t& below, uint32_t& bad, bool& flushed,
+                                              Flush&& flush)
 {
     uint32_t nown = 0;
 #pragma unroll
     for (int u = 0; u < kRoundTiles; ++u) {
         if (a0 + u * 64 < b) {
             const bool valid = a0 + u * 64 + lane < b;
-            const uint32_t id = (uint32_t)idr[u];
+            const uint32_t idg = (uint32_t)idr[u];
+            const uint32_t id = idg - id_base;          // row of the call; wraps to a huge number below the range
             const uint32_t rel = id - (uint32_t)lo;
             const bool own = valid && rel < span;
             const uint64_t m = ballot64(own);
             if (TALLY) {
                 below += (uint32_t)__popcll(ballot64(valid && id < (uint32_t)lo));
-                bad += (uint32_t)__popcll(ballot64(valid && id >= V));
+                bad += (uint32_t)__popcll(ballot64(valid && idg >= V_total));
             }
             if (m) {
                 if (nown > cap - 64u) {
@@ -425,7 +431,8 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
     for (int r = 0; r < rounds; ++r) {
         const int a0 = a + r * kRoundPairs;
         if (r > 0) load_round(sh, j0, j1, ids0, off0, a0, b, lane, idr);
-        nown = own_pairs<true>(idr, a0, b, lane, lo, span, (uint32_t)p.V, list, (uint32_t)p.list_cap, below, bad, flushed, count_listed);
+        nown = own_pairs<true>(idr, a0, b, lane, lo, span, (uint32_t)p.id_base, (uint32_t)p.V_total, list,
+                               (uint32_t)p.list_cap, below, bad, flushed, count_listed);
         count_listed(list, nown);
     }
     if (lane == 0) {
@@ -593,7 +600,8 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
         if (rounds > 1) load_round(sh, j0, j1, ids0, off0, a0, b, lane, idr);
         uint32_t unused0 = 0, unused1 = 0;
         bool unused2 = false;
-        nown = own_pairs<false>(idr, a0, b, lane, lo, span, (uint32_t)p.V, list, (uint32_t)p.list_cap, unused0, unused1, unused2, rank_listed);
+        nown = own_pairs<false>(idr, a0, b, lane, lo, span, (uint32_t)p.id_base, (uint32_t)p.V_total, list,
+                                (uint32_t)p.list_cap, unused0, unused1, unused2, rank_listed);
         rank_listed(list, nown);
     }
 }
@@ -995,8 +1003,9 @@ void launch_combine(unsigned grid, hipStream_t stream, const CombineParams& cp)
         else fn<EPI_SCALE_BF16>(__VA_ARGS__);                      \
     } while (0)
 
-int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, int32_t V,
-                 const float* dense_in, void* dense_out, int epi, float scale, void* stream_v)
+// V rows are produced: ids id_base .. id_base + V - 1 of a vocabulary of V_total ids.
+int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, int32_t V, int32_t id_base,
+                 int32_t V_total, const float* dense_in, void* dense_out, int epi, float scale, void* stream_v)
 {
     Plan pl;
     make_plan(n, d, V, &pl);
@@ -1008,6 +1017,8 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     SortParams sp;
     sp.n = (int32_t)n;
     sp.V = V;
+    sp.id_base = id_base;
+    sp.V_total = V_total;
     sp.G = pl.G;
     sp.S = pl.S;
     sp.SL = pl.SL;
@@ -1162,8 +1173,10 @@ int validate_common(int64_t n_total, int32_t d, int32_t V, const float* dense_in
 
 int densify_shards(const int32_t* const* ids_k, const void* const* rows_k, const int64_t* n_k, int32_t k,
                    int32_t row_dtype, int32_t d, int32_t V, const float* dense_in, void* dense_out, int epi,
-                   float scale, void* stream)
+                   float scale, void* stream, int32_t v_begin = 0, int32_t v_end = -1)
 {
+    if (v_end < 0) v_end = V;
+    if (V <= 0 || v_begin < 0 || v_begin >= v_end || v_end > V) return TS_ERR_SHAPE;
     if (k < 1 || k > TS_MAX_SHARDS) return TS_ERR_SHAPE;
     if (row_dtype != TS_ROW_FP32 && row_dtype != TS_ROW_BF16) return TS_ERR_SHAPE;
     if (!ids_k || !rows_k || !n_k) return TS_ERR_NULL;
@@ -1173,7 +1186,7 @@ int densify_shards(const int32_t* const* ids_k, const void* const* rows_k, const
         n_total += n_k[j];
         if (n_total >= ((int64_t)1 << 31)) return TS_ERR_OVERFLOW;
     }
-    int rc = validate_common(n_total, d, V, dense_in, dense_out);
+    int rc = validate_common(n_total, d, v_end - v_begin, dense_in, dense_out);
     if (rc != TS_OK) return rc;
     ShardTable sh;
     memset(&sh, 0, sizeof sh);
@@ -1189,7 +1202,7 @@ int densify_shards(const int32_t* const* ids_k, const void* const* rows_k, const
         off += n_k[j];
     }
     for (int j = k; j <= TS_MAX_SHARDS; ++j) sh.off[j] = (int32_t)off;
-    return densify_impl(sh, n_total, row_dtype, d, V, dense_in, dense_out, epi, scale, stream);
+    return densify_impl(sh, n_total, row_dtype, d, v_end - v_begin, v_begin, V, dense_in, dense_out, epi, scale, stream);
 }
 
 }  // namespace
@@ -1227,6 +1240,15 @@ int ts_densify_scaled(const int32_t* const* ids_k, const void* const* rows_k, co
     if (out_dtype == TS_OUT_BF16 && out && (const void*)dense_in == out) return TS_ERR_SHAPE;
     const int epi = out_dtype == TS_OUT_BF16 ? EPI_SCALE_BF16 : (scale == 1.0f ? EPI_NONE : EPI_SCALE);
     return densify_shards(ids_k, rows_k, n_k, k, row_dtype, d, V, dense_in, out, epi, scale, stream);
+}
+
+int ts_densify_range(const int32_t* const* ids_k, const void* const* rows_k, const int64_t* n_k,
+                     int32_t k, int32_t row_dtype, int32_t d, int32_t V, int32_t v_begin, int32_t v_end,
+                     const float* dense_in, float* dense_out, void* stream)
+{
+    if (v_end < 0) return TS_ERR_SHAPE;
+    return densify_shards(ids_k, rows_k, n_k, k, row_dtype, d, V, dense_in, dense_out, EPI_NONE, 1.0f, stream,
+                          v_begin, v_end);
 }
 
 int ts_fusion_place(int64_t capacity_bytes, int64_t used_bytes, int32_t d, int32_t V, int32_t out_dtype,

@@ -156,6 +156,21 @@ def test_scaled_entry_point_checks_and_fusion_placement(lib):
     assert lib.ts_fusion_place(2 ** 62, 0, 2 ** 31 - 1, 2 ** 31 - 1, 0, C.byref(o), C.byref(u)) == ts.TS_ERR_OVERFLOW
 
 
+def test_range_entry_point_checks(lib):
+    ts.ts_bind_workspace(None)
+    fake = 0x1000
+    ids = (C.c_void_p * 1)(fake)
+    n = (C.c_int64 * 1)(4)
+    f = lambda v0, v1, V=16: lib.ts_densify_range(ids, ids, n, 1, 0, 8, V, v0, v1, None, fake, None)
+    assert f(-1, 4) == ts.TS_ERR_SHAPE
+    assert f(4, 4) == ts.TS_ERR_SHAPE
+    assert f(5, 4) == ts.TS_ERR_SHAPE
+    assert f(0, 17) == ts.TS_ERR_SHAPE
+    assert f(0, -1) == ts.TS_ERR_SHAPE
+    assert f(0, 1, 0) == ts.TS_ERR_SHAPE
+    assert f(3, 9) == ts.TS_ERR_WORKSPACE        # passes every check, nothing bound
+
+
 def test_tuning_setters_validate(lib):
     assert lib.ts_set_piece_tokens(7) == ts.TS_ERR_SHAPE
     assert lib.ts_set_piece_tokens(0) == ts.TS_OK

@@ -1,0 +1,105 @@
+"""GPU parity of ts_densify_range (one owner's rows [v_begin, v_end) of the result): every
+range is compared with the same rows of the CPU checker's result for the whole vocabulary."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1905_04035_amd import binding as ts
+from paper_1905_04035_amd import workloads as wl
+
+from parity import TOL, DEV, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def run_range(w, v0, v1, dense=True, in_place=False):
+    V, d = w.V, w.d
+    Vr = v1 - v0
+    dn = to_dev(np.ascontiguousarray(w.dense_in[v0:v1])) if dense else None
+    out = dn if in_place else torch.full((Vr, d), float("nan"), dtype=torch.float32, device=DEV)
+    ws = ts.Workspace(max(w.n_total, 1), d, Vr, DEV)
+    try:
+        ts.ts_densify_range([to_dev(i) for i in w.ids], [to_dev(r) for r in w.rows], w.row_dtype, d, V, v0, v1,
+                            dn, out)
+        torch.cuda.synchronize()
+        count, row_start, perm, n_valid, n_bad = ts.ts_last_views(Vr, w.n_total)
+        uniq = ts.ts_unique_ids(min(max(w.n_total, 1), Vr))
+        host = out.cpu().numpy()
+    finally:
+        ws.close()
+    return dict(out=host, count=count.numpy(), row_start=row_start.numpy(), perm=perm.numpy(), n_valid=n_valid,
+                n_bad=n_bad, unique_ids=uniq.numpy())
+
+
+def check_range(w, r, v0, v1, exact_bits=False, **kw):
+    g = run_range(w, v0, v1, **kw)
+    ids, _ = w.concatenated()
+    inside = (ids >= v0) & (ids < v1)
+    assert np.array_equal(g["count"], r.count[v0:v1])
+    assert g["n_valid"] == int(inside.sum())
+    assert g["n_bad"] == r.n_bad                      # only ids outside the whole vocabulary are bad
+    assert np.array_equal(g["row_start"], np.concatenate([[0], np.cumsum(r.count[v0:v1])]).astype(np.int32))
+    assert np.array_equal(g["unique_ids"], r.unique_ids[(r.unique_ids >= v0) & (r.unique_ids < v1)] - v0)
+    want_perm = np.flatnonzero(inside)[np.argsort(ids[inside], kind="stable")].astype(np.int32)
+    assert np.array_equal(g["perm"], want_perm)
+    out, ref = g["out"], r.out[v0:v1]
+    untouched = r.count[v0:v1] == 0
+    assert np.array_equal(out[untouched].view(np.uint32), ref[untouched].view(np.uint32))
+    if exact_bits:
+        assert np.array_equal(out.view(np.uint32), ref.view(np.uint32))
+    else:
+        err = np.abs(out.astype(np.float64) - r.exact[v0:v1])
+        assert (err <= TOL * r.abs_sum[v0:v1]).all()
+    return g
+
+
+def test_owners_of_four_uneven_ranges_of_the_base_configuration():
+    w = wl.make("transformer_base")
+    r = oracle.densify(w.ids, w.rows, w.d, w.V, w.dense_in)
+    total = 0
+    for v0, v1 in [(0, 5000), (5000, 5001), (5001, 30000), (30000, w.V)]:
+        total += check_range(w, r, v0, v1)["n_valid"]
+    assert total == w.n_total
+    check_range(w, r, 0, w.V)           # the whole vocabulary: ts_densify_multi
+
+
+def test_eight_equal_owners_of_the_stress_configuration():
+    w = wl.make("multi_shard_stress")
+    r = oracle.densify(w.ids, w.rows, w.d, w.V, w.dense_in)
+    step = w.V // 8
+    hot = int(np.argmax(r.count))
+    for o in (0, hot // step, 7):       # the first, the last and the owner of the hottest row
+        g = check_range(w, r, o * step, (o + 1) * step)
+    assert r.count[hot] > 90000
+
+
+@pytest.mark.parametrize("ids", ["zipf", "single", "uniform"])
+def test_small_integer_values_bit_exact_in_every_range(ids):
+    w = wl.make_custom(V=3001, d=260, n_list=[9000, 30000], ids=ids, seed=81, integer_values=True)
+    r = oracle.densify(w.ids, w.rows, w.d, w.V, w.dense_in)
+    for v0, v1 in [(0, 1), (1, 1000), (1000, 3000), (3000, 3001), (0, 3001)]:
+        check_range(w, r, v0, v1, exact_bits=True)
+
+
+def test_ids_outside_the_vocabulary_are_bad_ids_of_other_owners_are_not():
+    w = wl.make_custom(V=500, d=64, n_list=[4000, 100], seed=82)
+    w.ids[0][::7] = -1
+    w.ids[0][3::11] = 500
+    w.ids[0][5::13] = np.iinfo(np.int32).max
+    w.ids[0][6::17] = np.iinfo(np.int32).min
+    r = oracle.densify(w.ids, w.rows, w.d, w.V, w.dense_in)
+    assert r.n_bad > 1000
+    for v0, v1 in [(0, 250), (250, 500), (100, 101), (499, 500)]:
+        check_range(w, r, v0, v1)
+
+
+def test_no_dense_operand_in_place_and_bf16_rows():
+    w = wl.make_custom(V=3000, d=256, n_list=[5000, 1000], seed=83)
+    r0 = oracle.densify(w.ids, w.rows, w.d, w.V, None)
+    check_range(w, r0, 700, 2900, dense=False)
+    r = oracle.densify(w.ids, w.rows, w.d, w.V, w.dense_in)
+    check_range(w, r, 700, 2900, in_place=True)
+    wb = wl.make_custom(V=3000, d=264, n_list=[20000], seed=84, row_dtype=wl.ROW_BF16)
+    rb = oracle.densify(wb.ids, wb.rows, wb.d, wb.V, wb.dense_in, wb.row_dtype)
+    check_range(wb, rb, 1234, 2345)
