@@ -378,7 +378,7 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
 {
     // [kSortWaves][part] counts, then [2][part] per-id totals and starts, then
     // [kSortWaves][list_cap] lists of owned pairs
-    extern __shared__ uint32_t cnt[];
+    extern __shared__ __align__(16) uint32_t cnt[];
     __shared__ uint32_t red[3 * kSortWaves];
 
     const int tid = threadIdx.x;
@@ -401,8 +401,6 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
     uint32_t* const id_start = id_total + part;
     uint32_t* const list = id_start + part + w * p.list_cap;
 
-    for (int i = tid; i < kSortWaves * part; i += 1024) cnt[i] = 0u;
-
     const int t0 = sl * p.SL;
     const int t1 = (int)min((int64_t)p.n, (int64_t)t0 + p.SL);
     const int L = p.SL / kSortWaves;
@@ -420,6 +418,34 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
 
     int32_t idr[kRoundTiles];
     if (rounds > 0) load_round(sh, j0, j1, ids0, off0, a, b, lane, idr);
+
+    const size_t GV = (size_t)p.G * part;
+    if (MODE == SORT_SCATTER) {
+        // Every id's count in all slices and in the slices before this one (thread tid speaks
+        // for ids lo + tid, lo + tid + 1024, ...), sixteen loads in flight at a time, fetched
+        // here so that their latency runs beside the ids' and the clearing of the tables.
+        // Kept where the scan below finds them.
+        for (int i = tid; i < part; i += 1024) {
+            uint32_t total = 0, pre = 0;
+            for (int sb = 0; sb < p.S; sb += 16) {
+                uint32_t x[16];
+#pragma unroll
+                for (int q = 0; q < 16; ++q)
+                    x[q] = sb + q < p.S ? p.tot[(size_t)(sb + q) * GV + lo + i] : 0u;
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    total += x[q];
+                    if (sb + q < sl) pre += x[q];
+                }
+            }
+            id_total[i] = total;
+            id_start[i] = pre;
+        }
+    }
+    {
+        u4* const c4 = reinterpret_cast<u4*>(cnt);
+        for (int i = tid; i < kSortWaves * part / 4; i += 1024) c4[i] = (u4)(0u);
+    }
     __syncthreads();
 
     // pass 1: list the owned pairs, count them per (wavefront, id); count what lies below the part
@@ -447,7 +473,6 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
         bad_wg += red[kSortWaves + ww];
     }
 
-    const size_t GV = (size_t)p.G * part;
     uint32_t base = below_wg, nbad = bad_wg;       // first sorted position of the part; bad ids
     if (MODE == SORT_COUNT) {
         if (tid == 0) {
@@ -485,20 +510,9 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
             continue;
         }
         uint32_t total = mine, pre = 0;
-        if (MODE == SORT_SCATTER) {
-            // the id's count in every slice, eight loads in flight at a time
-            total = 0;
-            for (int sb = 0; sb < p.S; sb += 8) {
-                uint32_t x[8];
-#pragma unroll
-                for (int q = 0; q < 8; ++q)
-                    x[q] = (idt && sb + q < p.S) ? p.tot[(size_t)(sb + q) * GV + lo + i] : 0u;
-#pragma unroll
-                for (int q = 0; q < 8; ++q) {
-                    total += x[q];
-                    if (sb + q < sl) pre += x[q];
-                }
-            }
+        if (MODE == SORT_SCATTER && idt) {
+            total = id_total[i];        // fetched at the start of the kernel, by this thread
+            pre = id_start[i];
         }
         const uint32_t incl = wave_inclusive_scan(total, lane);
         if (lane == 63) red[2 * kSortWaves + w] = incl;
