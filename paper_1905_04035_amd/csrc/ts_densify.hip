@@ -10,10 +10,11 @@
 // caller's stream, no host synchronisation, no allocation:
 //
 //   sort_kernel     stable counting sort of the pairs by id.  Work-group (g, s) owns `part`
-//                   consecutive ids (128 .. 1024) and slice s of the pairs; its 16
-//                   wavefronts load their sub-slices into registers, count owned pairs
-//                   into LDS-private tables, an exclusive scan turns the counts into
-//                   offsets, and a second walk hands every owned pair its final position.
+//                   consecutive ids (128 .. 2048) and slice s of the pairs; its 16
+//                   wavefronts load their sub-slices into registers, list the pairs the
+//                   work-group owns in LDS, count them into LDS-private tables, an
+//                   exclusive scan turns the counts into offsets, and a walk over the
+//                   lists hands every owned pair its final position.
 //                   A part's first position is the number of pairs with a smaller id,
 //                   which the work-group counts itself while it scans, so parts never
 //                   wait for one another.  With one slice (up to 16384 pairs) this is a

@@ -145,6 +145,22 @@ def test_piece_sizes_and_exact_boundaries(piece):
         ts.ts_set_piece_tokens(0)
 
 
+@pytest.mark.parametrize("part", [64, 512, 2048])
+@pytest.mark.parametrize("ids", ["single", "zipf", "uniform"])
+def test_sort_part_sizes_and_lists_of_owned_pairs(part, ids):
+    # parts of 2048 ids leave LDS for short lists of owned pairs only: a wavefront that owns more
+    # (one id taking every pair is the extreme) flushes its list and rebuilds it when it ranks
+    ts.ts_set_sort_part(part)
+    try:
+        # one slice; several slices; more than 64 slices' worth, so several rounds per wavefront
+        for n_list in ([5000], [20000, 30000], [1200000]):
+            w = wl.make_custom(V=3000, d=8, n_list=n_list, ids=ids, zipf_s=1.4, seed=part + len(n_list),
+                               integer_values=True)
+            _case(w, mode="multi", exact_bits=True)
+    finally:
+        ts.ts_set_sort_part(0)
+
+
 @pytest.mark.parametrize("mib", [0, 1, 4096])
 def test_result_does_not_depend_on_the_overlapped_copy(mib):
     w = wl.make_custom(V=5000, d=512, n_list=[6000, 3000], seed=46)
