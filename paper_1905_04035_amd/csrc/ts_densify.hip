@@ -67,10 +67,7 @@ static_assert(sizeof(SortedPair) == 32, "two 16-byte accesses per record");
 
 constexpr int kMaxPart = 2048;     // most ids one sort work-group owns (LDS: 18 x part x 4 B + 8 KiB of lists = 152 KiB)
 constexpr int kMinPart = 128;
-#ifndef TS_BIG_COPY_ROWS
-#define TS_BIG_COPY_ROWS 2
-#endif
-constexpr int kBigCopyRows = TS_BIG_COPY_ROWS;   // rows per wavefront in the copying work-groups of 1024 threads
+constexpr int kBigCopyRows = 2;    // rows per wavefront in the copying work-groups of 1024 threads
 constexpr int kSortWaves = 16;     // wavefronts per sort work-group
 constexpr int kColBlock = 256;     // fp32 columns per wavefront item (64 lanes x 4)
 constexpr int kMaxSlices = 64;
@@ -942,11 +939,11 @@ void make_plan(int64_t n, int32_t d, int32_t V, Plan* pl)
         pl->S = (int32_t)S;
         pl->SL = (int32_t)SL;
     }
-    // ids per sort work-group: smaller parts shorten the sort (fewer owned pairs per tile),
-    // but every sorting work-group holds half of a compute unit and slows the copy that
-    // runs beside it; about 64 work-groups per slice measured best
-    // (with several slices the scan of every slice by every part dominates: the largest parts
-    // that still give every compute unit a work-group)
+    // ids per sort work-group: smaller parts shorten the sort (fewer owned pairs per
+    // work-group), but every sorting work-group holds half of a compute unit and slows the
+    // copy that runs beside it; about 64 work-groups per slice measured best
+    // (with several slices every part looks at every slice, and that dominates: the largest
+    // parts that still give every compute unit a work-group)
     int part = (pl->S > 1 && (int64_t)((V + kMaxPart - 1) / kMaxPart) * pl->S >= 256) ? kMaxPart : 1024;
     while (pl->S == 1 && part > kMinPart && (int64_t)((V + part - 1) / part) < 64) part >>= 1;
     if (g_part_override) part = g_part_override;
