@@ -167,3 +167,22 @@ def test_runs_with_epilogue_are_bit_identical():
     a, _ = run_scaled(w, 0.2, ts.TS_OUT_BF16)
     b, _ = run_scaled(w, 0.2, ts.TS_OUT_BF16)
     assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_shapes_scales_and_outputs(seed):
+    rng = np.random.default_rng(3000 + seed)
+    V = int(rng.choice([1, 3, 64, 513, 2048, 5000, 40000]))
+    d = int(rng.choice([4, 8, 12, 256, 260, 264, 1024, 1100]))
+    k = int(rng.choice([1, 1, 2, 5]))
+    top = int(rng.choice([0, 10, 1000, 20000, 40000]))
+    n_list = [int(x) for x in rng.integers(0, top + 1, size=k)]
+    exact = seed % 2 == 0
+    w = wl.make_custom(V=V, d=d, n_list=n_list, ids=["zipf", "uniform", "single"][seed % 3],
+                       zipf_s=float(rng.choice([1.05, 1.3, 2.0])), seed=3000 + seed,
+                       row_dtype=wl.ROW_BF16 if seed % 4 == 1 else wl.ROW_FP32, integer_values=exact)
+    scale = float(rng.choice([0.5, -2.0, 0.0625])) if exact else float(rng.choice([1.0 / 3.0, -0.7, 1e-3, 1.0]))
+    out_dtype = ts.TS_OUT_BF16 if seed % 3 != 2 else ts.TS_OUT_FP32
+    check_scaled(w, scale, out_dtype, exact_bits=exact, dense=(seed % 5 != 0),
+                 in_place=(out_dtype == ts.TS_OUT_FP32 and seed % 5 != 0 and seed % 2 == 1))
+    check_scaled(w, scale, ts.TS_OUT_FP32, exact_bits=exact, dense=(seed % 5 != 0))

@@ -103,3 +103,22 @@ def test_no_dense_operand_in_place_and_bf16_rows():
     wb = wl.make_custom(V=3000, d=264, n_list=[20000], seed=84, row_dtype=wl.ROW_BF16)
     rb = oracle.densify(wb.ids, wb.rows, wb.d, wb.V, wb.dense_in, wb.row_dtype)
     check_range(wb, rb, 1234, 2345)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_ranges(seed):
+    rng = np.random.default_rng(4000 + seed)
+    V = int(rng.choice([2, 65, 513, 2048, 5000, 40000]))
+    d = int(rng.choice([4, 8, 256, 260, 1024]))
+    k = int(rng.choice([1, 2, 4]))
+    top = int(rng.choice([10, 1000, 20000, 40000]))
+    n_list = [int(x) for x in rng.integers(0, top + 1, size=k)]
+    exact = seed % 2 == 0
+    w = wl.make_custom(V=V, d=d, n_list=n_list, ids=["zipf", "uniform", "single"][seed % 3],
+                       zipf_s=float(rng.choice([1.05, 1.3, 2.0])), seed=4000 + seed, integer_values=exact)
+    if seed % 4 == 0 and len(w.ids[0]):
+        w.ids[0][:: max(1, len(w.ids[0]) // 7)] = V + 3
+    r = oracle.densify(w.ids, w.rows, w.d, w.V, w.dense_in)
+    cuts = sorted(set([0, V] + [int(x) for x in rng.integers(0, V + 1, size=3)]))
+    for v0, v1 in zip(cuts[:-1], cuts[1:]):
+        check_range(w, r, v0, v1, exact_bits=exact)
