@@ -207,6 +207,20 @@ def main():
         ms_per_step_with_events = (time.perf_counter() - t2) * 1e3 / args.steps
         kernel_ms = ts.ts_profile_end(args.steps)
 
+    # a third pass: every call bracketed by its own pair of events on the stream (median and
+    # minimum of single calls; the event packets add a few microseconds to each)
+    per_call = None
+    if use_events:
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+        evs[0].record(stream)
+        for i in range(args.steps):
+            step(i)
+            evs[i + 1].record(stream)
+        torch.cuda.synchronize()
+        us = np.array([evs[i].elapsed_time(evs[i + 1]) * 1e3 for i in range(args.steps)])
+        per_call = {"median_us": round(float(np.median(us)), 2), "min_us": round(float(us.min()), 2),
+                    "calls": int(args.steps), "measured": "one event pair per call, same stream"}
+
     alg = algorithmic_bytes(n, d, V, elem, out_elem)
     gbps = alg / (ms_per_step * 1e-3) / 1e9
     rows_per_s = n / (ms_per_step * 1e-3)
@@ -297,6 +311,7 @@ def main():
         "gathered_vs_dense_bytes": [gathered, dense_b],
         "parity_ok": parity_ok,
         "launch_split": info,
+        "per_call_events": per_call,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
