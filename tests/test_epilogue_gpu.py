@@ -186,3 +186,42 @@ def test_random_shapes_scales_and_outputs(seed):
     check_scaled(w, scale, out_dtype, exact_bits=exact, dense=(seed % 5 != 0),
                  in_place=(out_dtype == ts.TS_OUT_FP32 and seed % 5 != 0 and seed % 2 == 1))
     check_scaled(w, scale, ts.TS_OUT_FP32, exact_bits=exact, dense=(seed % 5 != 0))
+
+
+def test_scaled_and_range_calls_can_be_captured_in_a_hip_graph():
+    # both enqueue kernels only; every replay must give the eager call's bits, also with eager
+    # calls through the same workspace between the replays
+    from paper_1905_04035_amd import binding
+    w = wl.make_custom(V=6000, d=512, n_list=[30000, 5000], zipf_s=1.3, seed=91)      # three sort slices
+    ids_d = [to_dev(i) for i in w.ids]
+    rows_d = [to_dev(r) for r in w.rows]
+    dn = to_dev(w.dense_in)
+    v0, v1 = 1000, 4500
+    dn_slice = dn[v0:v1].contiguous()
+    ws = ts.Workspace(w.n_total, w.d, w.V, DEV)
+    try:
+        eager_s = torch.empty((w.V, w.d), dtype=torch.int16, device=DEV)
+        eager_r = torch.empty_like(dn_slice)
+        ts.ts_densify_scaled(ids_d, rows_d, w.row_dtype, w.d, w.V, dn, eager_s, 0.125)
+        ts.ts_densify_range(ids_d, rows_d, w.row_dtype, w.d, w.V, v0, v1, dn_slice, eager_r)
+        torch.cuda.synchronize()
+        out_s = torch.zeros_like(eager_s)
+        out_r = torch.zeros_like(eager_r)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            ts.ts_densify_scaled(ids_d, rows_d, w.row_dtype, w.d, w.V, dn, out_s, 0.125)
+            ts.ts_densify_range(ids_d, rows_d, w.row_dtype, w.d, w.V, v0, v1, dn_slice, out_r)
+        for rep in range(3):
+            out_s.zero_()
+            out_r.zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out_s, eager_s), f"scaled: replay {rep} differs from the eager call"
+            assert torch.equal(out_r, eager_r), f"range: replay {rep} differs from the eager call"
+            other = torch.empty_like(dn)
+            binding.ts_densify_multi([ids_d[1][: 100 * (rep + 1)]], [rows_d[1][: 100 * (rep + 1)]], w.row_dtype,
+                                     w.d, w.V, dn, other)
+            torch.cuda.synchronize()
+    finally:
+        ws.close()
