@@ -310,3 +310,24 @@ def test_random_shapes_and_options(seed):
             w.ids[0][b] = V + int(rng.integers(0, 5))
     mode = "multi" if (k > 1 or seed % 2) else "single"
     _case(w, mode=mode, dense=(seed % 7 != 0), in_place=(seed % 6 == 1), exact_bits=exact)
+
+
+def test_kernel_timing_events_for_benchmarks():
+    w = wl.make_custom(V=4000, d=256, n_list=[9000], seed=61)
+    ids_d, rows_d, dn = to_dev(w.ids[0]), to_dev(w.rows[0]), to_dev(w.dense_in)
+    out = torch.empty_like(dn)
+    ws = ts.Workspace(w.n_total, w.d, w.V, DEV)
+    try:
+        ts.ts_profile_begin(3)
+        for _ in range(5):                      # only the first three calls are timed
+            ts.ts_densify(ids_d, rows_d, w.d, w.V, dn, out)
+        torch.cuda.synchronize()
+        ms = ts.ts_profile_end(3)
+        assert len(ms) == 3 and all(0.0 < x < 10.0 for x in ms)
+        ts.ts_densify(ids_d, rows_d, w.d, w.V, dn, out)      # recording has stopped
+        torch.cuda.synchronize()
+        assert ts.ts_profile_end(3) == []
+        r = run_oracle(w)
+        assert np.all(np.abs(out.cpu().numpy().astype(np.float64) - r.exact) <= TOL * r.abs_sum)
+    finally:
+        ws.close()
