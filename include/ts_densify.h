@@ -242,7 +242,7 @@ int ts_profile_end(float* ms_out, int32_t capacity, int32_t* n_out);
 
 /*
  * Tuning.  piece_tokens: sorted positions handled by one wavefront item of the
- * row-reduce kernel (8, 16 or 32; 0 = choose from n).  Changes the fixed
+ * row-reduce kernel (8, 16 or 32; 0 = choose from n and the row type).  Changes the fixed
  * summation order (still deterministic) and the workspace size.
  */
 int ts_set_piece_tokens(int32_t piece_tokens);

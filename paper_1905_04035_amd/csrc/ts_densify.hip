@@ -17,7 +17,7 @@
 //                   lists hands every owned pair its final position.
 //                   A part's first position is the number of pairs with a smaller id,
 //                   which the work-group counts itself while it scans, so parts never
-//                   wait for one another.  With one slice (up to 16384 pairs) this is a
+//                   wait for one another.  With one slice (up to 32768 pairs) this is a
 //                   single launch; with more, a counting launch fills a [slice][id]
 //                   table first.  The sort leaves one 32-byte record per sorted pair.
 //   reduce_kernel   the HBM-bound kernel.  Wavefront items come in two kinds, heavy
@@ -73,8 +73,9 @@ constexpr int kSortWaves = 16;     // wavefronts per sort work-group
 constexpr int kColBlock = 256;     // fp32 columns per wavefront item (64 lanes x 4)
 constexpr int kMaxSlices = 64;
 constexpr int kSliceTokens = 16384;
-constexpr int kFusedSortMax = 16384;   // up to here one launch sorts everything
-constexpr int kPieceSmallMax = 32768;  // up to here pieces of 16 positions, above 32
+constexpr int kFusedSortMax = 32768;   // up to here one launch sorts everything (measured against two launches)
+constexpr int kPieceSmallMax = 16384;  // up to here pieces of 16 positions, above 32 (bf16 rows read 16 bytes
+                                       // per lane: always 16) -- measured
 constexpr int64_t kOverlapSortBytes = 48ll << 20;      // about what HBM moves while a sort launch runs
 constexpr int64_t kOverlapCombineBytes = 32ll << 20;   // same for the combine launch
 constexpr int kOneLevelPieces = 1024;  // up to this many pieces the combine is one launch
@@ -302,7 +303,7 @@ enum { SORT_FUSED = 0, SORT_COUNT = 1, SORT_SCATTER = 2 };
 
 // One wavefront walks its sub-slice [a, b) in rounds of kRoundTiles tiles of 64 pairs.
 // All ids of a round are loaded before any is used, so a round costs one memory
-// latency; with a single round (every slice of at most 16384 pairs) the ids stay in
+// latency; with a single round (slices of at most 16384 pairs) the ids stay in
 // registers between the counting and the ranking pass.
 constexpr int kRoundTiles = 16;
 constexpr int kRoundPairs = kRoundTiles * 64;
@@ -919,13 +920,13 @@ int g_prof_used = 0;
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-int piece_tokens_for(int64_t n)
+int piece_tokens_for(int64_t n, bool wide_bf16)
 {
     if (g_piece_override) return g_piece_override;
-    return n <= kPieceSmallMax ? 16 : 32;
+    return (wide_bf16 || n <= kPieceSmallMax) ? 16 : 32;
 }
 
-void make_plan(int64_t n, int32_t d, int32_t V, Plan* pl)
+void make_plan(int64_t n, int32_t d, int32_t V, int32_t C, Plan* pl)
 {
     if (n <= kFusedSortMax) {
         pl->S = 1;
@@ -950,7 +951,7 @@ void make_plan(int64_t n, int32_t d, int32_t V, Plan* pl)
     if (g_part_override) part = g_part_override;
     pl->part = part;
     pl->G = (V + part - 1) / part;
-    pl->C = piece_tokens_for(n);
+    pl->C = C;
     pl->NB = (int32_t)((n + pl->C - 1) / pl->C);
     // the combine adds a cut row's partial rows in segments; with few pieces one segment holds
     // any row and a single combine launch does
@@ -1033,8 +1034,9 @@ void launch_combine(unsigned grid, hipStream_t stream, const CombineParams& cp)
 int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, int32_t V, int32_t id_base,
                  int32_t V_total, const float* dense_in, void* dense_out, int epi, float scale, void* stream_v)
 {
+    const bool wide = row_dtype == TS_ROW_BF16 && (d % 8) == 0;     // 16-byte loads of bf16 rows
     Plan pl;
-    make_plan(n, d, V, &pl);
+    make_plan(n, d, V, piece_tokens_for(n, wide), &pl);
     if (!g_ws || (int64_t)pl.total > g_ws_bytes) return TS_ERR_WORKSPACE;
     if ((int64_t)pl.NB * pl.ncb + V >= ((int64_t)1 << 31) - 8) return TS_ERR_OVERFLOW;
     hipStream_t stream = (hipStream_t)stream_v;
@@ -1070,12 +1072,13 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     // share of the rows copied blindly would be overwritten: no blind copy then)
     // (defaults: a fixed part plus a part in proportion to the pairs, like the time that the
     // sort and the combine take)
-    const int64_t sixteenths = n >= kFusedSortMax ? 16 : n * 16 / kFusedSortMax;
+    const int64_t sixteenths = n * 16 / 16384;
     const int64_t budget = g_overlap_sort >= 0 ? g_overlap_sort : (pl.S == 1 ? kOverlapSortBytes * (32 + sixteenths) / 48 : 0);
     int64_t rows_per_launch = (in_place || (pl.S > 1 && epi != EPI_NONE)) ? 0 : budget / ((int64_t)8 * d);
     rows_per_launch = rows_per_launch / (kBigCopyRows * kSortWaves) * (kBigCopyRows * kSortWaves);
     // rows copied by the combine launch, taken from the end
-    const int64_t budget_c = g_overlap_combine >= 0 ? g_overlap_combine : kOverlapCombineBytes * (16 + sixteenths) / 32;
+    const int64_t budget_c = g_overlap_combine >= 0 ? g_overlap_combine
+                                                    : kOverlapCombineBytes * (16 + (sixteenths < 16 ? sixteenths : 16)) / 32;
     int64_t rows_tail = (skip_untouched || pl.NB == 0) ? 0 : budget_c / ((int64_t)8 * d);
     rows_tail = rows_tail / (kBigCopyRows * kSortWaves) * (kBigCopyRows * kSortWaves);
     if (rows_tail > V) rows_tail = V;
@@ -1110,7 +1113,6 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     rp.V = V;
     rp.d = d;
     rp.C = pl.C;
-    const bool wide = row_dtype == TS_ROW_BF16 && (d % 8) == 0;     // 16-byte loads of bf16 rows
     rp.ncb = wide ? (d + 2 * kColBlock - 1) / (2 * kColBlock) : pl.ncb;
     rp.n_piece_items = pl.NB * rp.ncb;
     rp.count = sp.count;
@@ -1316,10 +1318,10 @@ int ts_workspace_bytes(int64_t n_total, int32_t d, int32_t V, int64_t* bytes)
     if (!bytes) return TS_ERR_NULL;
     if (n_total < 0 || V <= 0 || d <= 0 || (d % 4) != 0) return TS_ERR_SHAPE;
     if (n_total >= ((int64_t)1 << 31)) return TS_ERR_OVERFLOW;
-    Plan a, b;
-    make_plan(n_total, d, V, &a);
-    make_plan(n_total < kPieceSmallMax ? n_total : kPieceSmallMax, d, V, &b);
-    *bytes = (int64_t)(a.total > b.total ? a.total : b.total);
+    // the smallest pieces a call of this size can use: the most pieces, the largest workspace
+    Plan a;
+    make_plan(n_total, d, V, piece_tokens_for(n_total, true), &a);
+    *bytes = (int64_t)a.total;
     return TS_OK;
 }
 
