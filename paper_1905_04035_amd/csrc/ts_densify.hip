@@ -1068,12 +1068,16 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     const bool in_place = (const void*)dense_in == (const void*)dense_out;
     const bool skip_untouched = in_place && epi == EPI_NONE;
     // rows copied by the sort launches: about as many bytes as HBM moves while a sort runs
-    // (a multi-slice sort keeps the whole GPU busy by itself, and with that many pairs a large
-    // share of the rows copied blindly would be overwritten: no blind copy then)
+    // (a sort of many slices keeps the whole GPU busy by itself, and with that many pairs a
+    // large share of the rows copied blindly would be overwritten: no blind copy then)
     // (defaults: a fixed part plus a part in proportion to the pairs, like the time that the
     // sort and the combine take)
     const int64_t sixteenths = n * 16 / 16384;
-    const int64_t budget = g_overlap_sort >= 0 ? g_overlap_sort : (pl.S == 1 ? kOverlapSortBytes * (32 + sixteenths) / 48 : 0);
+    // (a sort of a few slices leaves compute units idle, and a smaller blind copy beside each of
+    // its two launches still pays: +4 % at 3-4 slices; from 8 slices on it only slows the sort)
+    const int64_t budget_multi = pl.S <= 4 ? (32ll << 20) : (pl.S <= 6 ? (16ll << 20) : 0);
+    const int64_t budget = g_overlap_sort >= 0 ? g_overlap_sort
+                                               : (pl.S == 1 ? kOverlapSortBytes * (32 + sixteenths) / 48 : budget_multi);
     int64_t rows_per_launch = (in_place || (pl.S > 1 && epi != EPI_NONE)) ? 0 : budget / ((int64_t)8 * d);
     rows_per_launch = rows_per_launch / (kBigCopyRows * kSortWaves) * (kBigCopyRows * kSortWaves);
     // rows copied by the combine launch, taken from the end
