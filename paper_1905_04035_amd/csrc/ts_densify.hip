@@ -76,7 +76,6 @@ constexpr int kSliceTokens = 16384;
 constexpr int kFusedSortMax = 32768;   // up to here one launch sorts everything (measured against two launches)
 constexpr int kPieceSmallMax = 16384;  // up to here pieces of 16 positions, above 32 (bf16 rows read 16 bytes
                                        // per lane: always 16) -- measured
-constexpr int64_t kOverlapSortBytes = 48ll << 20;      // about what HBM moves while a sort launch runs
 constexpr int64_t kOverlapCombineBytes = 32ll << 20;   // same for the combine launch
 constexpr int kOneLevelPieces = 1024;  // up to this many pieces the combine is one launch
 constexpr int kSegmentPieces = 256;    // beyond: segments of this many pieces, then a second launch
@@ -1067,17 +1066,18 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     // sorted must go, because the reduce kernel would read scaled values.
     const bool in_place = (const void*)dense_in == (const void*)dense_out;
     const bool skip_untouched = in_place && epi == EPI_NONE;
-    // rows copied by the sort launches: about as many bytes as HBM moves while a sort runs
-    // (a sort of many slices keeps the whole GPU busy by itself, and with that many pairs a
-    // large share of the rows copied blindly would be overwritten: no blind copy then)
-    // (defaults: a fixed part plus a part in proportion to the pairs, like the time that the
-    // sort and the combine take)
+    // Rows copied by the sort launches: about as many bytes as HBM moves while a sort runs
+    // (measured defaults).  One slice: 32 MiB plus 1 MiB per 1024 pairs; beyond 16384 pairs the
+    // wavefronts walk their shares in two rounds and the sort takes about 8 us longer: 48 MiB
+    // more.  A sort of a few slices leaves compute units idle, and a smaller blind copy beside
+    // each of its two launches still pays (+4 % at 3-4 slices); a sort of many slices keeps the
+    // whole GPU busy by itself, and with that many pairs a large share of the rows copied
+    // blindly would be overwritten: no blind copy then.
     const int64_t sixteenths = n * 16 / 16384;
-    // (a sort of a few slices leaves compute units idle, and a smaller blind copy beside each of
-    // its two launches still pays: +4 % at 3-4 slices; from 8 slices on it only slows the sort)
+    const int64_t budget_single = ((n <= 16384 ? 32ll : 80ll) << 20) + (n / 1024 << 20);
     const int64_t budget_multi = pl.S <= 4 ? (32ll << 20) : (pl.S <= 6 ? (16ll << 20) : 0);
     const int64_t budget = g_overlap_sort >= 0 ? g_overlap_sort
-                                               : (pl.S == 1 ? kOverlapSortBytes * (32 + sixteenths) / 48 : budget_multi);
+                                               : (pl.S == 1 ? budget_single : budget_multi);
     int64_t rows_per_launch = (in_place || (pl.S > 1 && epi != EPI_NONE)) ? 0 : budget / ((int64_t)8 * d);
     rows_per_launch = rows_per_launch / (kBigCopyRows * kSortWaves) * (kBigCopyRows * kSortWaves);
     // rows copied by the combine launch, taken from the end
