@@ -1081,7 +1081,10 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     int64_t rows_per_launch = (in_place || (pl.S > 1 && epi != EPI_NONE)) ? 0 : budget / ((int64_t)8 * d);
     rows_per_launch = rows_per_launch / (kBigCopyRows * kSortWaves) * (kBigCopyRows * kSortWaves);
     // rows copied by the combine launch, taken from the end
+    // (with several slices most rows receive pairs and the combine has many more entries to walk:
+    // a small copy measured best)
     const int64_t budget_c = g_overlap_combine >= 0 ? g_overlap_combine
+                             : pl.S > 1             ? (4ll << 20)
                                                     : kOverlapCombineBytes * (16 + (sixteenths < 16 ? sixteenths : 16)) / 32;
     int64_t rows_tail = (skip_untouched || pl.NB == 0) ? 0 : budget_c / ((int64_t)8 * d);
     rows_tail = rows_tail / (kBigCopyRows * kSortWaves) * (kBigCopyRows * kSortWaves);
