@@ -17,7 +17,7 @@
 //                   lists hands every owned pair its final position.
 //                   A part's first position is the number of pairs with a smaller id,
 //                   which the work-group counts itself while it scans, so parts never
-//                   wait for one another.  With one slice (up to 32768 pairs) this is a
+//                   wait for one another.  With one slice (up to 49152 pairs) this is a
 //                   single launch; with more, a counting launch fills a [slice][id]
 //                   table first.  The sort leaves one 32-byte record per sorted pair.
 //   reduce_kernel   the HBM-bound kernel.  Wavefront items come in two kinds, heavy
@@ -73,7 +73,7 @@ constexpr int kSortWaves = 16;     // wavefronts per sort work-group
 constexpr int kColBlock = 256;     // fp32 columns per wavefront item (64 lanes x 4)
 constexpr int kMaxSlices = 64;
 constexpr int kSliceTokens = 16384;
-constexpr int kFusedSortMax = 32768;   // up to here one launch sorts everything (measured against two launches)
+constexpr int kFusedSortMax = 49152;   // up to here one launch sorts everything (measured against two launches)
 constexpr int kPieceSmallMax = 16384;  // up to here pieces of 16 positions, above 32 (bf16 rows read 16 bytes
                                        // per lane: always 16) -- measured
 constexpr int64_t kOverlapCombineBytes = 32ll << 20;   // same for the combine launch
@@ -328,23 +328,25 @@ __device__ __forceinline__ void load_round(const ShardTable& sh, int j0, int j1,
 
 // Walks the tiles of a round and appends the pairs that this work-group owns to the
 // wavefront's list, in input order (tiles in order, lanes in order).  An entry is
-// (id - lo) << 10 | position of the pair in the round.  Every work-group looks at every
-// pair of its slice but owns few of them: counting and ranking walk the short list.
-// The list holds cap entries (a whole round when LDS allows, kListCap otherwise); when the
-// next tile might not fit, flush(list, count) consumes what is listed and the list starts
-// again (flushed tells the caller that the list no longer holds the whole round).  Returns
-// the entries left in the list.
+// (id - lo) << 21 | position of the pair in the wavefront's sub-slice (ids per part <= 2^11,
+// pairs per sub-slice <= 2^21).  Every work-group looks at every pair of its slice but owns
+// few of them: counting and ranking walk the short list, which is kept from round to round.
+// The list holds cap entries (1024 when LDS allows, kListCap otherwise); when the next tile
+// might not fit, flush(list, count) consumes what is listed and the list starts again
+// (flushed tells the caller that the list no longer holds all owned pairs).  nown is the
+// number of entries in the list, before and after.
 // With TALLY the pairs with a valid id below the part and those with an id outside [0, V)
 // are counted as well (wave-uniform counts).
 constexpr int kListCap = 128;
 
+constexpr int kListPosBits = 21;
+
 template <bool TALLY, typename Flush>
-__device__ __forceinline__ uint32_t own_pairs(const int32_t (&idr)[kRoundTiles], int a0, int b, int lane, int lo,
-                                              uint32_t span, uint32_t id_base, uint32_t V_total, uint32_t* list,
-                                              uint32_t cap, uint32_t& below, uint32_t& bad, bool& flushed,
-                                              Flush&& flush)
+__device__ __forceinline__ void own_pairs(const int32_t (&idr)[kRoundTiles], int a0, int b, uint32_t pos0, int lane,
+                                          int lo, uint32_t span, uint32_t id_base, uint32_t V_total, uint32_t* list,
+                                          uint32_t cap, uint32_t& nown, uint32_t& below, uint32_t& bad,
+                                          bool& flushed, Flush&& flush)
 {
-    uint32_t nown = 0;
 #pragma unroll
     for (int u = 0; u < kRoundTiles; ++u) {
         if (a0 + u * 64 < b) {
@@ -364,12 +366,11 @@ __device__ __forceinline__ uint32_t own_pairs(const int32_t (&idr)[kRoundTiles],
                     nown = 0;
                     flushed = true;
                 }
-                if (own) list[nown + lanes_below(m)] = (rel << 10) | (uint32_t)(u * 64 + lane);
+                if (own) list[nown + lanes_below(m)] = (rel << kListPosBits) | (pos0 + (uint32_t)(u * 64 + lane));
                 nown += (uint32_t)__popcll(m);
             }
         }
     }
-    return nown;
 }
 
 template <int MODE, int EPI>
@@ -451,15 +452,15 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
     uint32_t below = 0, bad = 0, nown = 0;
     bool flushed = false;
     auto count_listed = [&](const uint32_t* l, uint32_t cnt_l) {
-        for (uint32_t t = lane; t < cnt_l; t += 64) atomicAdd(&mycnt[l[t] >> 10], 1u);
+        for (uint32_t t = lane; t < cnt_l; t += 64) atomicAdd(&mycnt[l[t] >> kListPosBits], 1u);
     };
     for (int r = 0; r < rounds; ++r) {
         const int a0 = a + r * kRoundPairs;
         if (r > 0) load_round(sh, j0, j1, ids0, off0, a0, b, lane, idr);
-        nown = own_pairs<true>(idr, a0, b, lane, lo, span, (uint32_t)p.id_base, (uint32_t)p.V_total, list,
-                               (uint32_t)p.list_cap, below, bad, flushed, count_listed);
-        count_listed(list, nown);
+        own_pairs<true>(idr, a0, b, (uint32_t)(r * kRoundPairs), lane, lo, span, (uint32_t)p.id_base,
+                        (uint32_t)p.V_total, list, (uint32_t)p.list_cap, nown, below, bad, flushed, count_listed);
     }
+    count_listed(list, nown);
     if (lane == 0) {
         red[w] = below;
         red[kSortWaves + w] = bad;
@@ -552,15 +553,14 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
     // input order and wavefronts own consecutive sub-slices, so the sort is stable.  Per 64
     // list entries: one LDS read of the running positions, a scalar loop over the distinct
     // ids among them (pairs of one id are ranked by lane), one LDS write by the last lane of
-    // each id.  With a single round whose owned pairs fitted the list, the list of pass 1 is
-    // still there; otherwise the round is walked again.
-    int a0 = a;
+    // each id.  If the owned pairs fitted the list, the list of pass 1 is still there; otherwise
+    // the sub-slice is walked again.
     auto rank_listed = [&](const uint32_t* l, uint32_t cnt_l) {
         for (uint32_t e0 = 0; e0 < cnt_l; e0 += 64) {
             const bool own = e0 + lane < cnt_l;
             const uint32_t ent = own ? l[e0 + lane] : 0u;
-            const uint32_t rel = ent >> 10;
-            const int idx = a0 + (int)(ent & 1023u);
+            const uint32_t rel = ent >> kListPosBits;
+            const int idx = a + (int)(ent & ((1u << kListPosBits) - 1u));
             uint64_t m = ballot64(own);
             const uint32_t basev = own ? mycnt[rel] : 0u;
             const uint32_t tot_l = own ? id_total[rel] : 0u;
@@ -604,19 +604,20 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
             }
         }
     };
-    if (rounds == 1 && !flushed) {
+    if (!flushed) {
         rank_listed(list, nown);
         return;
     }
+    nown = 0;
     for (int r = 0; r < rounds; ++r) {
-        a0 = a + r * kRoundPairs;
+        const int a0 = a + r * kRoundPairs;
         if (rounds > 1) load_round(sh, j0, j1, ids0, off0, a0, b, lane, idr);
         uint32_t unused0 = 0, unused1 = 0;
         bool unused2 = false;
-        nown = own_pairs<false>(idr, a0, b, lane, lo, span, (uint32_t)p.id_base, (uint32_t)p.V_total, list,
-                                (uint32_t)p.list_cap, unused0, unused1, unused2, rank_listed);
-        rank_listed(list, nown);
+        own_pairs<false>(idr, a0, b, (uint32_t)(r * kRoundPairs), lane, lo, span, (uint32_t)p.id_base,
+                         (uint32_t)p.V_total, list, (uint32_t)p.list_cap, nown, unused0, unused1, unused2, rank_listed);
     }
+    rank_listed(list, nown);
 }
 
 // ------------------------------------------------------------------ reduce
@@ -1067,24 +1068,25 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     const bool in_place = (const void*)dense_in == (const void*)dense_out;
     const bool skip_untouched = in_place && epi == EPI_NONE;
     // Rows copied by the sort launches: about as many bytes as HBM moves while a sort runs
-    // (measured defaults).  One slice: 32 MiB plus 1 MiB per 1024 pairs; beyond 16384 pairs the
-    // wavefronts walk their shares in two rounds and the sort takes about 8 us longer: 48 MiB
-    // more.  A sort of a few slices leaves compute units idle, and a smaller blind copy beside
+    // (measured defaults).  One slice: 32 MiB plus 1 MiB per 1024 pairs up to 16384 pairs, 2.5 MiB
+    // per 1024 pairs beyond (the wavefronts then walk their shares in several rounds).  A sort
+    // of a few slices leaves compute units idle, and a smaller blind copy beside
     // each of its two launches still pays (+4 % at 3-4 slices); a sort of many slices keeps the
     // whole GPU busy by itself, and with that many pairs a large share of the rows copied
     // blindly would be overwritten: no blind copy then.
     const int64_t sixteenths = n * 16 / 16384;
-    const int64_t budget_single = ((n <= 16384 ? 32ll : 80ll) << 20) + (n / 1024 << 20);
+    const int64_t budget_single = n <= 16384 ? (32ll << 20) + (n / 1024 << 20)
+                                             : (48ll << 20) + (n - 16384) / 1024 * (5ll << 19);
     const int64_t budget_multi = pl.S <= 4 ? (32ll << 20) : (pl.S <= 6 ? (16ll << 20) : 0);
     const int64_t budget = g_overlap_sort >= 0 ? g_overlap_sort
                                                : (pl.S == 1 ? budget_single : budget_multi);
     int64_t rows_per_launch = (in_place || (pl.S > 1 && epi != EPI_NONE)) ? 0 : budget / ((int64_t)8 * d);
     rows_per_launch = rows_per_launch / (kBigCopyRows * kSortWaves) * (kBigCopyRows * kSortWaves);
     // rows copied by the combine launch, taken from the end
-    // (with several slices most rows receive pairs and the combine has many more entries to walk:
-    // a small copy measured best)
+    // (with many pairs most rows receive some and the combine has many more entries to walk: a
+    // small copy measured best)
     const int64_t budget_c = g_overlap_combine >= 0 ? g_overlap_combine
-                             : pl.S > 1             ? (4ll << 20)
+                             : (pl.S > 1 || n > 32768) ? (4ll << 20)
                                                     : kOverlapCombineBytes * (16 + (sixteenths < 16 ? sixteenths : 16)) / 32;
     int64_t rows_tail = (skip_untouched || pl.NB == 0) ? 0 : budget_c / ((int64_t)8 * d);
     rows_tail = rows_tail / (kBigCopyRows * kSortWaves) * (kBigCopyRows * kSortWaves);
