@@ -5,7 +5,7 @@
 //   reduce            sum_kernel: dense tensors added in list order, one streaming pass
 //   convert + reduce  the dense tensor (or sum_kernel's sum of several) becomes dense_in of
 //                     ts_densify_multi, which converts the slice gradients and adds them
-//   gather            concat: every gradient as slices, laid end to end -- iota_kernel writes
+//   gather            concat: every gradient as slices, laid end to end -- ids_kernel writes
 //                     ids 0 .. V-1 for a dense tensor, copy kernels move ids and value rows
 // This file sits on top of the public entry points; it shares no state with them.
 #include <hip/hip_runtime.h>
