@@ -17,7 +17,7 @@
 //                   lists hands every owned pair its final position.
 //                   A part's first position is the number of pairs with a smaller id,
 //                   which the work-group counts itself while it scans, so parts never
-//                   wait for one another.  With one slice (up to 49152 pairs) this is a
+//                   wait for one another.  With one slice (up to 57344 pairs) this is a
 //                   single launch; with more, a counting launch fills a [slice][id]
 //                   table first.  The sort leaves one 32-byte record per sorted pair.
 //   reduce_kernel   the HBM-bound kernel.  Wavefront items come in two kinds, heavy
@@ -73,7 +73,7 @@ constexpr int kSortWaves = 16;     // wavefronts per sort work-group
 constexpr int kColBlock = 256;     // fp32 columns per wavefront item (64 lanes x 4)
 constexpr int kMaxSlices = 64;
 constexpr int kSliceTokens = 16384;
-constexpr int kFusedSortMax = 49152;   // up to here one launch sorts everything (measured against two launches)
+constexpr int kFusedSortMax = 57344;   // up to here one launch sorts everything (measured against two launches)
 constexpr int kPieceSmallMax = 16384;  // up to here pieces of 16 positions, above 32 (bf16 rows read 16 bytes
                                        // per lane: always 16) -- measured
 constexpr int64_t kOverlapCombineBytes = 32ll << 20;   // same for the combine launch

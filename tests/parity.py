@@ -51,9 +51,10 @@ def run_gpu(w: wl.Workload, mode="auto", group=1, in_place=False, dense=True):
         count, row_start, perm, n_valid, n_bad = ts.ts_last_views(V, w.n_total)
         uniq = ts.ts_unique_ids(min(max(w.n_total, 1), V))
         out_h = out.cpu().numpy()
+        info = ts.ts_last_launch_info()
     finally:
         ws.close()
-    return dict(out=out_h, count=count.numpy(), row_start=row_start.numpy(), perm=perm.numpy(),
+    return dict(info=info, out=out_h, count=count.numpy(), row_start=row_start.numpy(), perm=perm.numpy(),
                 n_valid=n_valid, n_bad=n_bad, unique_ids=uniq.numpy())
 
 

@@ -192,7 +192,7 @@ def test_scaled_and_range_calls_can_be_captured_in_a_hip_graph():
     # both enqueue kernels only; every replay must give the eager call's bits, also with eager
     # calls through the same workspace between the replays
     from paper_1905_04035_amd import binding
-    w = wl.make_custom(V=6000, d=512, n_list=[30000, 5000], zipf_s=1.3, seed=91)      # three sort slices
+    w = wl.make_custom(V=6000, d=512, n_list=[60000, 5000], zipf_s=1.3, seed=91)      # two sort launches
     ids_d = [to_dev(i) for i in w.ids]
     rows_d = [to_dev(r) for r in w.rows]
     dn = to_dev(w.dense_in)

@@ -170,7 +170,7 @@ def test_result_does_not_depend_on_the_overlapped_copy(mib):
         _case(w, mode="multi")
         got = run_gpu(w, mode="multi")
         _case(w, mode="multi", dense=False)
-        wb = wl.make_custom(V=3000, d=256, n_list=[40000], seed=47)      # two sort launches
+        wb = wl.make_custom(V=3000, d=256, n_list=[70000], seed=47)      # two sort launches
         _case(wb)
     finally:
         ts.ts_set_overlap_bytes(-1, -1)
@@ -331,3 +331,14 @@ def test_kernel_timing_events_for_benchmarks():
         assert np.all(np.abs(out.cpu().numpy().astype(np.float64) - r.exact) <= TOL * r.abs_sum)
     finally:
         ws.close()
+
+
+@pytest.mark.parametrize("n", [16385, 20000, 40000, 57344, 57345])
+@pytest.mark.parametrize("ids", ["zipf", "single"])
+def test_sizes_around_the_one_launch_sort_limit(n, ids):
+    # up to 57344 pairs one launch sorts everything, a wavefront walking its share in several rounds
+    # of 1024 pairs and keeping its list of owned pairs from round to round ('single': the list of
+    # the owning work-group overflows and the share is walked again); one pair more takes two launches
+    w = wl.make_custom(V=4000, d=8, n_list=[n], ids=ids, zipf_s=1.3, seed=n, integer_values=True)
+    worst, g, r = _case(w, mode="single", exact_bits=True)
+    assert g["info"]["sort_slices"] == (1 if n <= 57344 else 4)
