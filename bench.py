@@ -47,6 +47,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="transformer_big",
                     choices=["transformer_base", "transformer_big", "large_batch_bf16", "multi_shard_stress"])
+    ap.add_argument("--tokens", type=int, default=0,
+                    help="instead of a named workload: one worker's share at a per-worker batch of this many "
+                         "tokens (the paper's scaling runs use 2,048 to 25,600, Section 5): V=32768, d=1024, "
+                         "fp32, an encoder and a decoder contribution of that many pairs each, Zipf 1.1")
     ap.add_argument("--sets", type=int, default=3, help="independent buffer sets to rotate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--overlap-mib", type=float, default=-1.0,
@@ -88,7 +92,12 @@ def main():
     if args.piece_tokens:
         ts.ts_set_piece_tokens(args.piece_tokens)
 
-    w = wl.make(args.workload)
+    if args.tokens > 0:
+        args.workload = f"per_worker_batch_{args.tokens}_tokens"
+        w = wl.make_custom(V=32768, d=1024, n_list=[args.tokens, args.tokens], zipf_s=1.1,
+                           seed=190504035 + args.tokens, sigma_rows=0.01, sigma_dense=1.0)
+    else:
+        w = wl.make(args.workload)
     V, d, n = w.V, w.d, w.n_total
     elem = 2 if w.row_dtype == wl.ROW_BF16 else 4
     multi = args.workload == "multi_shard_stress"
