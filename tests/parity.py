@@ -10,8 +10,8 @@ from paper_1905_04035_amd import workloads as wl
 # fp32 outputs must satisfy |gpu - exact| <= TOL * (sum of |terms| of that element).
 # The library adds at most C <= 32 rows in sequence inside a piece, then the pieces of a
 # cut row in 16 contiguous shares, the shares in sequence, and dense_in last; with fp32
-# unit round-off 2^-24 the first-order bound is (depth - 1) * 2^-24 * sum|terms|, far
-# below 1e-5 for every case tested here (see error_depth below).
+# unit round-off 2^-24 the first-order bound is (depth - 1) * 2^-24 * sum|terms|, below 1e-5
+# for every case tested here (see error_depth and error_bound below).
 TOL = 1e-5
 DEV = "cuda:0"
 
@@ -94,8 +94,20 @@ def check(g, r: oracle.OracleResult, w: wl.Workload, exact_bits=False):
     return float(np.max(err / scale))
 
 
-def error_depth(count_max: int, C: int) -> int:
-    """Additions on the longest chain a term can take: C inside a piece, the pieces of a share
-    (16 shares at most... 4 per column block at d = 1024), the shares, dense_in."""
-    pieces = -(-count_max // C) + 1
-    return C + -(-pieces // 4) + 16 + 1
+def error_depth(count_max: int, C: int, pieces_in_call: int) -> int:
+    """Additions on the longest chain a term of the fullest row can take: C inside a piece; the
+    pieces of a wavefront's share (16 shares), the shares, dense_in.  With more than 1024 pieces
+    in the call a row is combined in segments of 256 pieces first, then the segment sums the
+    same way."""
+    P = -(-count_max // C) + 1
+    if count_max <= C:
+        return count_max + 1
+    if pieces_in_call <= 1024:
+        return C + -(-P // 16) + 16 + 1
+    segments = -(-P // 256) + 1
+    return C + 16 + 16 + -(-segments // 16) + 16 + 1
+
+
+def error_bound(count_max: int, C: int, pieces_in_call: int) -> float:
+    """First-order bound on |err| / sum|terms| for fp32 sums in that order."""
+    return (error_depth(count_max, C, pieces_in_call) - 1) * 2.0 ** -24

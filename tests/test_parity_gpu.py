@@ -8,7 +8,7 @@ import oracle
 from paper_1905_04035_amd import binding as ts
 from paper_1905_04035_amd import workloads as wl
 
-from parity import TOL, check, run_gpu, run_oracle, to_dev, DEV
+from parity import TOL, check, error_bound, run_gpu, run_oracle, to_dev, DEV
 
 pytestmark = pytest.mark.gpu
 
@@ -342,3 +342,14 @@ def test_sizes_around_the_one_launch_sort_limit(n, ids):
     w = wl.make_custom(V=4000, d=8, n_list=[n], ids=ids, zipf_s=1.3, seed=n, integer_values=True)
     worst, g, r = _case(w, mode="single", exact_bits=True)
     assert g["info"]["sort_slices"] == (1 if n <= 57344 else 4)
+
+
+@pytest.mark.parametrize("name,group", [("transformer_big", 1), ("large_batch_bf16", 1), ("multi_shard_stress", 2)])
+def test_measured_error_stays_under_the_a_priori_bound(name, group):
+    # fp32 sums in the library's fixed order: the worst |err| / sum|terms| of a call must not
+    # exceed the first-order bound for its longest chain, which itself lies under the tolerance
+    w = wl.make(name)
+    worst, g, r = _case(w, mode="multi", group=group)
+    bound = error_bound(int(r.count.max()), g["info"]["piece_tokens"], g["info"]["pieces"])
+    assert bound < TOL
+    assert worst <= bound, (worst, bound)
