@@ -353,3 +353,13 @@ def test_measured_error_stays_under_the_a_priori_bound(name, group):
     bound = error_bound(int(r.count.max()), g["info"]["piece_tokens"], g["info"]["pieces"])
     assert bound < TOL
     assert worst <= bound, (worst, bound)
+
+
+def test_no_pairs_is_a_pass_through():
+    # Section 3, Algorithm 1: with nothing to accumulate the gradient passes through
+    w = wl.make_custom(V=777, d=132, n_list=[0], seed=62)
+    g = run_gpu(w)
+    assert np.array_equal(g["out"].view(np.uint32), w.dense_in.view(np.uint32))
+    assert g["n_valid"] == 0 and g["n_bad"] == 0 and len(g["unique_ids"]) == 0 and not g["count"].any()
+    z = run_gpu(w, dense=False)
+    assert np.array_equal(z["out"].view(np.uint32), np.zeros((777, 132), dtype=np.uint32))
