@@ -51,7 +51,9 @@ def main():
                     help="instead of a named workload: one worker's share at a per-worker batch of this many "
                          "tokens (the paper's scaling runs use 2,048 to 25,600, Section 5): V=32768, d=1024, "
                          "fp32, an encoder and a decoder contribution of that many pairs each, Zipf 1.1")
-    ap.add_argument("--sets", type=int, default=3, help="independent buffer sets to rotate over")
+    ap.add_argument("--sets", type=int, default=0,
+                    help="independent buffer sets to rotate over (0 = at least 3, and as many as it takes to "
+                         "pass 1 GB in all, so that no call finds its data in the 256 MB memory-side cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--overlap-mib", type=float, default=-1.0,
                     help="dense bytes copied beside each sort launch (tuning; -1 = library default)")
@@ -109,6 +111,9 @@ def main():
     def dev_rows(a):
         return torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).to(dev)
 
+    if args.sets <= 0:
+        per_set = 4 * V * d + out_elem * V * d + n * (4 + elem * d)
+        args.sets = max(3, -(-10 ** 9 // per_set))
     sets = []
     for _ in range(args.sets):
         s = dict(dense_in=torch.from_numpy(w.dense_in).to(dev),
