@@ -363,3 +363,12 @@ def test_no_pairs_is_a_pass_through():
     assert g["n_valid"] == 0 and g["n_bad"] == 0 and len(g["unique_ids"]) == 0 and not g["count"].any()
     z = run_gpu(w, dense=False)
     assert np.array_equal(z["out"].view(np.uint32), np.zeros((777, 132), dtype=np.uint32))
+
+
+def test_twenty_million_pairs():
+    # 64 slices of 312,500 pairs: every wavefront walks its share in 20 rounds; 625,000 pieces
+    w = wl.make_custom(V=3000, d=4, n_list=[12_000_000, 8_000_000], ids="zipf", zipf_s=1.2, seed=63,
+                       integer_values=True)
+    worst, g, r = _case(w, mode="multi")
+    assert g["info"]["sort_slices"] == 64 and g["info"]["pieces"] == 625000
+    assert int(r.count.max()) > 1_000_000
