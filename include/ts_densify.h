@@ -214,6 +214,16 @@ int ts_last_views(const int32_t** count, const int32_t** row_start, const void**
                   const int32_t** n_valid, const int32_t** n_bad_ids);
 
 /*
+ * The same, copied to host arrays, for tests and tools: waits for `stream`, then copies
+ * count [V] and row_start [V + 1] (int32), the first n_valid sorted records
+ * (TS_SORTED_PAIR_BYTES each; TS_ERR_CAPACITY if n_valid > sorted_capacity records) and
+ * the two scalars.  Any out-pointer may be NULL.  V is that of the most recent call (the
+ * number of rows of the range for ts_densify_range).  This call synchronises.
+ */
+int ts_read_views(int32_t* count_out, int32_t* row_start_out, void* sorted_out, int64_t sorted_capacity,
+                  int32_t* n_valid_out, int32_t* n_bad_ids_out, void* stream);
+
+/*
  * How the most recent call was split over its launches, for byte accounting in
  * benchmarks.  Writes 8 int32 to info (host): [0] piece_tokens C; [1] X: dense rows
  * [0, X) were copied beside the sort launches; [2] T: untouched rows in [X, T) were

@@ -60,6 +60,7 @@ def lib():
         l.ts_workspace_bytes.argtypes = [i64, i32, i32, vp]
         l.ts_bind_workspace.argtypes = [vp, i64]
         l.ts_last_views.argtypes = [vp, vp, vp, vp, vp]
+        l.ts_read_views.argtypes = [vp, vp, vp, i64, vp, vp, vp]
         l.ts_unique_ids.argtypes = [vp, vp, vp]
         l.ts_last_launch_info.argtypes = [vp]
         l.ts_profile_begin.argtypes = [i32]
@@ -73,7 +74,7 @@ def lib():
         for name in ("ts_densify", "ts_densify_bf16", "ts_densify_multi", "ts_buffer_bytes",
                      "ts_densify_scaled", "ts_fusion_place", "ts_densify_range",
                      "ts_accumulate_strategy", "ts_accumulate",
-                     "ts_workspace_bytes", "ts_bind_workspace", "ts_last_views", "ts_unique_ids",
+                     "ts_workspace_bytes", "ts_bind_workspace", "ts_last_views", "ts_read_views", "ts_unique_ids",
                      "ts_last_launch_info",
                      "ts_profile_begin", "ts_profile_end", "ts_set_piece_tokens", "ts_set_overlap_bytes", "ts_set_sort_part", "ts_set_combine_groups"):
             getattr(l, name).restype = C.c_int
@@ -270,38 +271,26 @@ class Workspace:
         self.tensor = None
 
 
-def ts_last_views(V: int, n: int):
-    """(count[V], row_start[V+1], perm[n_valid], n_valid, n_bad_ids) of the last call, copied to
-    the host after a synchronise; perm is the input position of every sorted pair."""
+def ts_read_views(V: int, n: int):
+    """(count[V], row_start[V+1], perm[n_valid], n_valid, n_bad_ids) of the last call as host
+    tensors (the library waits for the current stream and copies); perm is the input position of
+    every sorted pair."""
+    count = torch.empty(V, dtype=torch.int32)
+    row_start = torch.empty(V + 1, dtype=torch.int32)
+    records = torch.empty((max(n, 1), 8), dtype=torch.int32)        # TS_SORTED_PAIR_BYTES = 32
+    n_valid, n_bad = C.c_int32(0), C.c_int32(0)
+    _check(lib().ts_read_views(C.c_void_p(count.data_ptr()), C.c_void_p(row_start.data_ptr()),
+                               C.c_void_p(records.data_ptr()), n, C.byref(n_valid), C.byref(n_bad),
+                               _stream(None)), "ts_read_views")
+    return count, row_start, records[:n_valid.value, 3].contiguous(), n_valid.value, n_bad.value
+
+
+def ts_last_views():
+    """Device addresses (ints) of count, row_start, the sorted records, n_valid and n_bad_ids of
+    the last call, inside the bound workspace."""
     ptrs = [C.c_void_p() for _ in range(5)]
     _check(lib().ts_last_views(*[C.byref(p) for p in ptrs]), "ts_last_views")
-    torch.cuda.synchronize()
-
-    def fetch(ptr, count):
-        if count == 0:
-            return torch.empty(0, dtype=torch.int32)
-        host = torch.empty(count, dtype=torch.int32)
-        rc = _hip().hipMemcpy(C.c_void_p(host.data_ptr()), ptr, C.c_size_t(4 * count), C.c_int(2))
-        if rc != 0:
-            raise RuntimeError(f"hipMemcpy failed with {rc}")
-        return host
-
-    n_valid = int(fetch(ptrs[3], 1)[0])
-    n_bad = int(fetch(ptrs[4], 1)[0])
-    records = fetch(ptrs[2], 8 * min(n_valid, n)).view(-1, 8)      # TS_SORTED_PAIR_BYTES = 32
-    return fetch(ptrs[0], V), fetch(ptrs[1], V + 1), records[:, 3].contiguous(), n_valid, n_bad
-
-
-_hiprt = None
-
-
-def _hip():
-    global _hiprt
-    if _hiprt is None:
-        _hiprt = C.CDLL("libamdhip64.so")
-        _hiprt.hipMemcpy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int]
-        _hiprt.hipMemcpy.restype = C.c_int
-    return _hiprt
+    return tuple(p.value for p in ptrs)
 
 
 def ts_unique_ids(capacity: int, stream=None, device="cuda:0"):

@@ -1365,6 +1365,32 @@ int ts_last_views(const int32_t** count, const int32_t** row_start, const void**
     return TS_OK;
 }
 
+int ts_read_views(int32_t* count_out, int32_t* row_start_out, void* sorted_out, int64_t sorted_capacity,
+                  int32_t* n_valid_out, int32_t* n_bad_ids_out, void* stream)
+{
+    if (!g_ws || !g_have_last) return TS_ERR_WORKSPACE;
+    if (sorted_out && sorted_capacity < 0) return TS_ERR_SHAPE;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return TS_ERR_HIP;
+    const char* ws = (const char*)g_ws;
+    int32_t n_valid = 0, n_bad = 0;
+    if (hipMemcpy(&n_valid, ws + g_last_plan.off_nvalid, 4, hipMemcpyDeviceToHost) != hipSuccess) return TS_ERR_HIP;
+    if (hipMemcpy(&n_bad, ws + g_last_plan.off_nbad, 4, hipMemcpyDeviceToHost) != hipSuccess) return TS_ERR_HIP;
+    if (n_valid_out) *n_valid_out = n_valid;
+    if (n_bad_ids_out) *n_bad_ids_out = n_bad;
+    if (count_out && hipMemcpy(count_out, ws + g_last_plan.off_count, (size_t)g_last_V * 4, hipMemcpyDeviceToHost) != hipSuccess)
+        return TS_ERR_HIP;
+    if (row_start_out && hipMemcpy(row_start_out, ws + g_last_plan.off_row_start, ((size_t)g_last_V + 1) * 4,
+                                   hipMemcpyDeviceToHost) != hipSuccess)
+        return TS_ERR_HIP;
+    if (sorted_out) {
+        if ((int64_t)n_valid > sorted_capacity) return TS_ERR_CAPACITY;
+        if (n_valid > 0 && hipMemcpy(sorted_out, ws + g_last_plan.off_sorted, (size_t)n_valid * sizeof(SortedPair),
+                                     hipMemcpyDeviceToHost) != hipSuccess)
+            return TS_ERR_HIP;
+    }
+    return TS_OK;
+}
+
 int ts_last_launch_info(int32_t* info)
 {
     if (!info) return TS_ERR_NULL;

@@ -48,7 +48,7 @@ def run_gpu(w: wl.Workload, mode="auto", group=1, in_place=False, dense=True):
             rows_d = [to_dev(r) for r in rows_k]
             ts.ts_densify_multi(ids_d, rows_d, w.row_dtype, d, V, dn, out)
         torch.cuda.synchronize()
-        count, row_start, perm, n_valid, n_bad = ts.ts_last_views(V, w.n_total)
+        count, row_start, perm, n_valid, n_bad = ts.ts_read_views(V, w.n_total)
         uniq = ts.ts_unique_ids(min(max(w.n_total, 1), V))
         out_h = out.cpu().numpy()
         info = ts.ts_last_launch_info()

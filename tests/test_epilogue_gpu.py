@@ -39,7 +39,7 @@ def run_scaled(w, scale, out_dtype, group=1, dense=True, in_place=False, buffer_
         ts.ts_densify_scaled([to_dev(i) for i in ids_k], [to_dev(r) for r in rows_k], w.row_dtype, d, V, dn,
                              out, scale)
         torch.cuda.synchronize()
-        count, _, _, _, _ = ts.ts_last_views(V, w.n_total)
+        count, _, _, _, _ = ts.ts_read_views(V, w.n_total)
         host = out.cpu().numpy()
         if buf is not None:
             b = buf.cpu().numpy()

@@ -23,7 +23,7 @@ def run_range(w, v0, v1, dense=True, in_place=False):
         ts.ts_densify_range([to_dev(i) for i in w.ids], [to_dev(r) for r in w.rows], w.row_dtype, d, V, v0, v1,
                             dn, out)
         torch.cuda.synchronize()
-        count, row_start, perm, n_valid, n_bad = ts.ts_last_views(Vr, w.n_total)
+        count, row_start, perm, n_valid, n_bad = ts.ts_read_views(Vr, w.n_total)
         uniq = ts.ts_unique_ids(min(max(w.n_total, 1), Vr))
         host = out.cpu().numpy()
     finally:
