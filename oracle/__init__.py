@@ -8,6 +8,7 @@ from .reference import (  # noqa: F401
     OracleResult,
     buffer_bytes,
     densify,
+    densify_one_shot,
     densify_timed,
     unique_ids,
 )

@@ -3,8 +3,8 @@
 Algorithm 1 (Section 3) is TensorFlow's rule: fewer than two gradients pass through; if every
 gradient is a dense tensor they are summed (reduce); otherwise every gradient is turned into
 indexed slices and the slices are concatenated (gather).  A dense [V, d] tensor turned into
-slices is V slices, one per row, with ids 0 .. V-1 (Section 3: the dense gradient is converted
-"even though all the gradients being accumulated are dense").
+slices is V slices, one per row, with ids 0 .. V-1 (Section 3: the dense projection gradient is
+converted to slices as well, although it holds a value for every row).
 
 Algorithm 2 (Section 6) adds one branch before the gather: if at least one gradient is a dense
 tensor, every gradient is converted to a dense tensor and the dense tensors are summed.

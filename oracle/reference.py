@@ -27,7 +27,8 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        path = _build.build(force=False)
+        # TS_SANITIZE=1: the build with the address and undefined-behaviour sanitizers
+        path = _build.build(force=False, sanitize=os.environ.get("TS_SANITIZE") == "1")
         lib = C.CDLL(path)
         lib.oracle_accumulate.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32,
                                           C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -136,6 +137,36 @@ def buffer_bytes(k: int, N: int, d: int, V: int, row_dtype: int = ROW_FP32):
     return int(g[0]), int(dn[0])
 
 
+def _one_shot(lib, ids, rows, d, V, dn, row_dtype):
+    """One call of oracle_densify on marshalled arrays: (out, count, n_bad, seconds)."""
+    out = np.empty((V, d), dtype=np.float32)
+    count = np.zeros(V, dtype=np.int32)
+    n_bad = np.zeros(1, dtype=np.int64)
+    t0 = time.perf_counter()
+    rc = lib.oracle_densify(_ptr(ids), _ptr(rows), ids.size, d, V, row_dtype, _ptr(dn),
+                            _ptr(out), _ptr(count), _ptr(n_bad))
+    t1 = time.perf_counter()
+    if rc != 0:
+        raise MemoryError("oracle_densify could not allocate its accumulator")
+    return out, count, int(n_bad[0]), t1 - t0
+
+
+def densify_one_shot(ids: np.ndarray, rows: np.ndarray, d: int, V: int, dense_in: Optional[np.ndarray],
+                     row_dtype: int = ROW_FP32):
+    """(out, count, n_bad) of the one-shot form oracle_densify: the same definition as
+    densify() on a single contribution, with the function's own float64 array.  This is
+    the form densify_timed() times; the pins compare its output with densify()'s."""
+    lib = _load()
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    rows = _as_rows(rows, row_dtype, d)
+    assert rows.size == ids.size * d, (rows.shape, ids.shape, d)
+    dn = None if dense_in is None else np.ascontiguousarray(dense_in, dtype=np.float32)
+    if dn is not None:
+        assert dn.shape == (V, d)
+    out, count, n_bad, _ = _one_shot(lib, ids, rows, d, V, dn, row_dtype)
+    return out, count, n_bad
+
+
 def densify_timed(ids: np.ndarray, rows: np.ndarray, d: int, V: int, dense_in: Optional[np.ndarray],
                   row_dtype: int = ROW_FP32, repeats: int = 3) -> List[float]:
     """Seconds per call of the one-shot form (own zeroed float64 array, single
@@ -144,17 +175,9 @@ def densify_timed(ids: np.ndarray, rows: np.ndarray, d: int, V: int, dense_in: O
     ids = np.ascontiguousarray(ids, dtype=np.int32)
     rows = _as_rows(rows, row_dtype, d)
     dn = None if dense_in is None else np.ascontiguousarray(dense_in, dtype=np.float32)
-    out = np.empty((V, d), dtype=np.float32)
     times = []
     for it in range(repeats + 1):
-        count = np.zeros(V, dtype=np.int32)
-        n_bad = np.zeros(1, dtype=np.int64)
-        t0 = time.perf_counter()
-        rc = lib.oracle_densify(_ptr(ids), _ptr(rows), ids.size, d, V, row_dtype, _ptr(dn),
-                                _ptr(out), _ptr(count), _ptr(n_bad))
-        t1 = time.perf_counter()
-        if rc != 0:
-            raise MemoryError("oracle_densify could not allocate its accumulator")
+        seconds = _one_shot(lib, ids, rows, d, V, dn, row_dtype)[3]
         if it > 0:
-            times.append(t1 - t0)
+            times.append(seconds)
     return times

@@ -22,7 +22,9 @@ TS_ROW_FP32, TS_ROW_BF16 = 0, 1
 TS_OUT_FP32, TS_OUT_BF16 = 0, 1
 TS_MAX_SHARDS = 64
 
-LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libts_densify.so")
+# TS_SANITIZE=1 selects the build whose host code runs under ASan + UBSan (build.py, sanitize=True)
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)),
+                        "libts_densify_san.so" if os.environ.get("TS_SANITIZE") == "1" else "libts_densify.so")
 
 _lib = None
 

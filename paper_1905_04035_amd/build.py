@@ -7,6 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SRCS = [os.path.join(HERE, "csrc", f) for f in ("ts_densify.hip", "ts_accumulate.hip")]
 LIB = os.path.join(HERE, "libts_densify.so")
+LIB_SAN = os.path.join(HERE, "libts_densify_san.so")     # host code under ASan + UBSan (checks of the host logic)
 INCLUDE = os.path.join(ROOT, "include")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -18,10 +19,18 @@ FLAGS = [
 ]
 
 
-def build(force: bool = True, verbose: bool = False) -> str:
-    if not force and os.path.exists(LIB):
-        return LIB
-    cmd = [HIPCC] + FLAGS + ["-o", LIB] + SRCS
+SAN_FLAGS = ["-g", "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+             "-Xarch_host", "-fno-sanitize-recover=undefined", "-shared-libsan"]
+
+
+def build(force: bool = True, verbose: bool = False, sanitize: bool = False) -> str:
+    """sanitize=True: a second library whose HOST code runs under the address and
+    undefined-behaviour sanitizers (device code unchanged); the loading process must have
+    clang's shared sanitizer runtime preloaded."""
+    lib = LIB_SAN if sanitize else LIB
+    if not force and os.path.exists(lib):
+        return lib
+    cmd = [HIPCC] + FLAGS + (SAN_FLAGS if sanitize else []) + ["-o", lib] + SRCS
     if verbose:
         print(" ".join(cmd))
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -31,9 +40,9 @@ def build(force: bool = True, verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + err)
     if err.strip() and verbose:
         print(err)
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":
-    print(build(force=True, verbose=True))
+    print(build(force=True, verbose=True, sanitize="--sanitize" in sys.argv))
     sys.exit(0)

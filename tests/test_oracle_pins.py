@@ -86,6 +86,84 @@ def test_brute_force_tiny(seed):
     assert r.n_bad == int(((ids < 0) | (ids >= V)).sum())
 
 
+# ---------------------------------------------------------------- the one-shot form (the one that is timed)
+def _golden_inputs(g):
+    ids = np.array(g["ids"], dtype=np.int32)
+    if "rows_bf16_hex" in g:
+        rows = np.array([[int(x, 16) for x in r] for r in g["rows_bf16_hex"]], dtype=np.uint16)
+        dt = wl.ROW_BF16
+    else:
+        rows = np.array(g["rows"], dtype=np.float32)
+        dt = wl.ROW_FP32
+    dense = None if g["dense_in"] is None else np.array(g["dense_in"], dtype=np.float32)
+    return ids, rows, dt, dense
+
+
+@pytest.mark.parametrize("name", ["worked_case_shared_embedding.json", "worked_case_convert_only.json",
+                                  "worked_case_bf16_rows.json"])
+def test_one_shot_form_on_the_hand_worked_cases(name):
+    # oracle_densify (own float64 array, one call) is the form whose time is reported as the
+    # CPU baseline: it must give the hand-worked values (Section 4, Listing 1; Section 6,
+    # Algorithm 2) as well.
+    g = _load(name)
+    ids, rows, dt, dense = _golden_inputs(g)
+    out, count, n_bad = oracle.densify_one_shot(ids, rows, g["d"], g["V"], dense, dt)
+    assert np.array_equal(out, np.array(g["expected_out"], dtype=np.float32))
+    assert count.tolist() == g["expected_count"]
+    assert n_bad == g["expected_n_bad"]
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_one_shot_form_brute_force_tiny(seed):
+    rng = np.random.default_rng(100 + seed)
+    V = int(rng.integers(1, 9))
+    d = int(rng.integers(1, 9))
+    n = int(rng.integers(0, 17))
+    ids = rng.integers(-1, V + 1, size=n).astype(np.int32)      # includes out-of-range ids
+    rows = rng.standard_normal((n, d)).astype(np.float32)
+    dense = None if seed % 3 == 0 else rng.standard_normal((V, d)).astype(np.float32)
+    out, count, n_bad = oracle.densify_one_shot(ids, rows, d, V, dense)
+    want, cnt = _triple_loop(ids, rows, d, V, dense)
+    assert np.array_equal(out, want.astype(np.float32))
+    assert count.tolist() == cnt
+    assert n_bad == int(((ids < 0) | (ids >= V)).sum())
+
+
+@pytest.mark.parametrize("row_dtype", [wl.ROW_FP32, wl.ROW_BF16])
+@pytest.mark.parametrize("with_dense", [True, False])
+def test_one_shot_form_on_workload_tiny_with_bad_ids(row_dtype, with_dense):
+    # library scatter-add in float64 as the third opinion, then bit equality with the
+    # shard-by-shard form the parity tests use
+    w = wl.make_custom(V=1000, d=64, n_list=[2048], ids="uniform", seed=21, row_dtype=row_dtype)
+    ids, rows = w.concatenated()
+    ids = ids.copy()
+    ids[[3, 500, 2047]] = [-1, w.V, np.iinfo(np.int32).max]
+    dense = w.dense_in if with_dense else None
+    out, count, n_bad = oracle.densify_one_shot(ids, rows, w.d, w.V, dense, row_dtype)
+    ok = (ids >= 0) & (ids < w.V)
+    wide = wl.bf16_bits_to_fp32(rows) if row_dtype == wl.ROW_BF16 else rows
+    a = np.zeros((w.V, w.d), dtype=np.float64)
+    np.add.at(a, ids[ok], wide[ok].astype(np.float64))
+    base = np.zeros((w.V, w.d)) if dense is None else dense.astype(np.float64)
+    assert np.array_equal(count, np.bincount(ids[ok], minlength=w.V))
+    assert n_bad == 3
+    touched = count > 0
+    np.testing.assert_allclose(out[touched].astype(np.float64), (a + base)[touched], rtol=1e-6, atol=1e-30)
+    want_untouched = np.zeros((w.V, w.d), dtype=np.float32) if dense is None else dense
+    assert np.array_equal(out[~touched].view(np.uint32), want_untouched[~touched].view(np.uint32))
+    r = oracle.densify([ids], [rows], w.d, w.V, dense, row_dtype)
+    assert np.array_equal(out.view(np.uint32), r.out.view(np.uint32))
+    assert np.array_equal(count, r.count) and n_bad == r.n_bad
+
+
+def test_one_shot_form_transposed_rows_would_be_caught():
+    ids = np.array([0, 1, 0], dtype=np.int32)
+    rows = np.array([[1, 10], [100, 1000], [10000, 100000]], dtype=np.float32)
+    out, count, n_bad = oracle.densify_one_shot(ids, rows, 2, 2, None)
+    assert out.tolist() == [[10001.0, 100010.0], [100.0, 1000.0]]
+    assert count.tolist() == [2, 1] and n_bad == 0
+
+
 # ---------------------------------------------------------------- library scatter-adds
 def test_against_numpy_add_at_and_torch_index_add():
     w = wl.make("tiny")
