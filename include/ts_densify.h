@@ -69,7 +69,7 @@ enum { TS_ROW_FP32 = 0, TS_ROW_BF16 = 1 };
 int ts_densify(const int32_t* ids, const float* rows, int64_t n, int32_t d, int32_t V,
                const float* dense_in, float* dense_out, void* stream);
 
-/* Same, value rows stored as bf16 bit patterns; they are widened exactly and summed in fp32. */
+/* Same as ts_densify, value rows stored as bf16 bit patterns; they are widened exactly and summed in fp32. */
 int ts_densify_bf16(const int32_t* ids, const uint16_t* rows, int64_t n, int32_t d, int32_t V,
                     const float* dense_in, float* dense_out, void* stream);
 
@@ -216,12 +216,15 @@ int ts_last_views(const int32_t** count, const int32_t** row_start, const void**
 /*
  * The same, copied to host arrays, for tests and tools: waits for `stream`, then copies
  * count [V] and row_start [V + 1] (int32), the first n_valid sorted records
- * (TS_SORTED_PAIR_BYTES each; TS_ERR_CAPACITY if n_valid > sorted_capacity records) and
- * the two scalars.  Any out-pointer may be NULL.  V is that of the most recent call (the
- * number of rows of the range for ts_densify_range).  This call synchronises.
+ * (TS_SORTED_PAIR_BYTES each) and the two scalars.  Any out-pointer may be NULL.  V is that
+ * of the most recent call (the number of rows of the range for ts_densify_range), which the
+ * library knows and the caller states: count_out holds rows_capacity int32 and row_start_out
+ * rows_capacity + 1; TS_ERR_CAPACITY, with nothing written, if the last call's V exceeds
+ * rows_capacity, and likewise if n_valid exceeds sorted_capacity records.  This call
+ * synchronises.
  */
-int ts_read_views(int32_t* count_out, int32_t* row_start_out, void* sorted_out, int64_t sorted_capacity,
-                  int32_t* n_valid_out, int32_t* n_bad_ids_out, void* stream);
+int ts_read_views(int32_t* count_out, int32_t* row_start_out, int64_t rows_capacity, void* sorted_out,
+                  int64_t sorted_capacity, int32_t* n_valid_out, int32_t* n_bad_ids_out, void* stream);
 
 /*
  * How the most recent call was split over its launches, for byte accounting in

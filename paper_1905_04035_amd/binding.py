@@ -62,7 +62,7 @@ def lib():
         l.ts_workspace_bytes.argtypes = [i64, i32, i32, vp]
         l.ts_bind_workspace.argtypes = [vp, i64]
         l.ts_last_views.argtypes = [vp, vp, vp, vp, vp]
-        l.ts_read_views.argtypes = [vp, vp, vp, i64, vp, vp, vp]
+        l.ts_read_views.argtypes = [vp, vp, i64, vp, i64, vp, vp, vp]
         l.ts_unique_ids.argtypes = [vp, vp, vp]
         l.ts_last_launch_info.argtypes = [vp]
         l.ts_profile_begin.argtypes = [i32]
@@ -281,7 +281,7 @@ def ts_read_views(V: int, n: int):
     row_start = torch.empty(V + 1, dtype=torch.int32)
     records = torch.empty((max(n, 1), 8), dtype=torch.int32)        # TS_SORTED_PAIR_BYTES = 32
     n_valid, n_bad = C.c_int32(0), C.c_int32(0)
-    _check(lib().ts_read_views(C.c_void_p(count.data_ptr()), C.c_void_p(row_start.data_ptr()),
+    _check(lib().ts_read_views(C.c_void_p(count.data_ptr()), C.c_void_p(row_start.data_ptr()), V,
                                C.c_void_p(records.data_ptr()), n, C.byref(n_valid), C.byref(n_bad),
                                _stream(None)), "ts_read_views")
     return count, row_start, records[:n_valid.value, 3].contiguous(), n_valid.value, n_bad.value

@@ -910,6 +910,7 @@ int32_t g_combine_groups = 0;           // 0 = choose from the number of pieces
 void* g_ws = nullptr;
 int64_t g_ws_bytes = 0;
 Plan g_last_plan;
+void* g_last_ws = nullptr;              // the workspace the most recent call used (bound, or the built-in one)
 int32_t g_last_V = 0;
 int32_t g_last_info[8] = {0, 0, 0, 0, 0, 0, 0, 0};
 bool g_have_last = false;
@@ -1034,15 +1035,16 @@ void launch_combine(unsigned grid, hipStream_t stream, const CombineParams& cp)
 
 // V rows are produced: ids id_base .. id_base + V - 1 of a vocabulary of V_total ids.
 int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, int32_t V, int32_t id_base,
-                 int32_t V_total, const float* dense_in, void* dense_out, int epi, float scale, void* stream_v)
+                 int32_t V_total, const float* dense_in, void* dense_out, int epi, float scale, void* stream_v,
+                 void* ws_v, int64_t ws_bytes)
 {
     const bool wide = row_dtype == TS_ROW_BF16 && (d % 8) == 0;     // 16-byte loads of bf16 rows
     Plan pl;
     make_plan(n, d, V, piece_tokens_for(n, wide), &pl);
-    if (!g_ws || (int64_t)pl.total > g_ws_bytes) return TS_ERR_WORKSPACE;
+    if (!ws_v || (int64_t)pl.total > ws_bytes) return TS_ERR_WORKSPACE;
     if ((int64_t)pl.NB * pl.ncb + V >= ((int64_t)1 << 31) - 8) return TS_ERR_OVERFLOW;
     hipStream_t stream = (hipStream_t)stream_v;
-    char* ws = (char*)g_ws;
+    char* ws = (char*)ws_v;
 
     SortParams sp;
     sp.n = (int32_t)n;
@@ -1186,6 +1188,7 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
         if (hipGetLastError() != hipSuccess) return TS_ERR_HIP;
     }
     g_last_plan = pl;
+    g_last_ws = ws_v;
     g_last_V = V;
     g_last_info[0] = pl.C;
     g_last_info[1] = copy_done;
@@ -1210,8 +1213,13 @@ int validate_common(int64_t n_total, int32_t d, int32_t V, const float* dense_in
 
 int densify_shards(const int32_t* const* ids_k, const void* const* rows_k, const int64_t* n_k, int32_t k,
                    int32_t row_dtype, int32_t d, int32_t V, const float* dense_in, void* dense_out, int epi,
-                   float scale, void* stream, int32_t v_begin = 0, int32_t v_end = -1)
+                   float scale, void* stream, int32_t v_begin = 0, int32_t v_end = -1, void* ws = nullptr,
+                   int64_t ws_bytes = -1)
 {
+    if (ws_bytes < 0) {         // the bound workspace
+        ws = g_ws;
+        ws_bytes = g_ws_bytes;
+    }
     if (v_end < 0) v_end = V;
     if (V <= 0 || v_begin < 0 || v_begin >= v_end || v_end > V) return TS_ERR_SHAPE;
     if (k < 1 || k > TS_MAX_SHARDS) return TS_ERR_SHAPE;
@@ -1239,7 +1247,8 @@ int densify_shards(const int32_t* const* ids_k, const void* const* rows_k, const
         off += n_k[j];
     }
     for (int j = k; j <= TS_MAX_SHARDS; ++j) sh.off[j] = (int32_t)off;
-    return densify_impl(sh, n_total, row_dtype, d, v_end - v_begin, v_begin, V, dense_in, dense_out, epi, scale, stream);
+    return densify_impl(sh, n_total, row_dtype, d, v_end - v_begin, v_begin, V, dense_in, dense_out, epi, scale, stream,
+                        ws, ws_bytes);
 }
 
 }  // namespace
@@ -1355,8 +1364,8 @@ int ts_bind_workspace(void* ws, int64_t bytes)
 int ts_last_views(const int32_t** count, const int32_t** row_start, const void** sorted,
                   const int32_t** n_valid, const int32_t** n_bad_ids)
 {
-    if (!g_ws || !g_have_last) return TS_ERR_WORKSPACE;
-    const char* ws = (const char*)g_ws;
+    if (!g_last_ws || !g_have_last) return TS_ERR_WORKSPACE;
+    const char* ws = (const char*)g_last_ws;
     if (count) *count = (const int32_t*)(ws + g_last_plan.off_count);
     if (row_start) *row_start = (const int32_t*)(ws + g_last_plan.off_row_start);
     if (sorted) *sorted = (const void*)(ws + g_last_plan.off_sorted);
@@ -1365,16 +1374,19 @@ int ts_last_views(const int32_t** count, const int32_t** row_start, const void**
     return TS_OK;
 }
 
-int ts_read_views(int32_t* count_out, int32_t* row_start_out, void* sorted_out, int64_t sorted_capacity,
-                  int32_t* n_valid_out, int32_t* n_bad_ids_out, void* stream)
+int ts_read_views(int32_t* count_out, int32_t* row_start_out, int64_t rows_capacity, void* sorted_out,
+                  int64_t sorted_capacity, int32_t* n_valid_out, int32_t* n_bad_ids_out, void* stream)
 {
-    if (!g_ws || !g_have_last) return TS_ERR_WORKSPACE;
+    if (!g_last_ws || !g_have_last) return TS_ERR_WORKSPACE;
     if (sorted_out && sorted_capacity < 0) return TS_ERR_SHAPE;
+    // the lengths of count and row_start come from the last call, not from this caller
+    if ((count_out || row_start_out) && rows_capacity < (int64_t)g_last_V) return TS_ERR_CAPACITY;
     if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return TS_ERR_HIP;
-    const char* ws = (const char*)g_ws;
+    const char* ws = (const char*)g_last_ws;
     int32_t n_valid = 0, n_bad = 0;
     if (hipMemcpy(&n_valid, ws + g_last_plan.off_nvalid, 4, hipMemcpyDeviceToHost) != hipSuccess) return TS_ERR_HIP;
     if (hipMemcpy(&n_bad, ws + g_last_plan.off_nbad, 4, hipMemcpyDeviceToHost) != hipSuccess) return TS_ERR_HIP;
+    if (sorted_out && (int64_t)n_valid > sorted_capacity) return TS_ERR_CAPACITY;
     if (n_valid_out) *n_valid_out = n_valid;
     if (n_bad_ids_out) *n_bad_ids_out = n_bad;
     if (count_out && hipMemcpy(count_out, ws + g_last_plan.off_count, (size_t)g_last_V * 4, hipMemcpyDeviceToHost) != hipSuccess)
@@ -1383,7 +1395,6 @@ int ts_read_views(int32_t* count_out, int32_t* row_start_out, void* sorted_out, 
                                    hipMemcpyDeviceToHost) != hipSuccess)
         return TS_ERR_HIP;
     if (sorted_out) {
-        if ((int64_t)n_valid > sorted_capacity) return TS_ERR_CAPACITY;
         if (n_valid > 0 && hipMemcpy(sorted_out, ws + g_last_plan.off_sorted, (size_t)n_valid * sizeof(SortedPair),
                                      hipMemcpyDeviceToHost) != hipSuccess)
             return TS_ERR_HIP;
@@ -1402,8 +1413,8 @@ int ts_last_launch_info(int32_t* info)
 int ts_unique_ids(int32_t* unique_ids_out, int32_t* n_unique_out, void* stream)
 {
     if (!unique_ids_out || !n_unique_out) return TS_ERR_NULL;
-    if (!g_ws || !g_have_last) return TS_ERR_WORKSPACE;
-    const int32_t* count = (const int32_t*)((const char*)g_ws + g_last_plan.off_count);
+    if (!g_last_ws || !g_have_last) return TS_ERR_WORKSPACE;
+    const int32_t* count = (const int32_t*)((const char*)g_last_ws + g_last_plan.off_count);
     hipLaunchKernelGGL(unique_kernel, dim3(1), dim3(1024), 0, (hipStream_t)stream, count, g_last_V,
                        unique_ids_out, n_unique_out);
     return check_hip(hipGetLastError());

@@ -94,7 +94,7 @@ def test_argument_checks_happen_before_any_launch(lib):
     assert lib.ts_densify_multi(None, ids, n, 1, 0, 8, 16, None, fake, None) == ts.TS_ERR_NULL
     assert lib.ts_bind_workspace(C.c_void_p(fake + 8), 1 << 20) == ts.TS_ERR_ALIGN
     assert lib.ts_last_views(None, None, None, None, None) == ts.TS_ERR_WORKSPACE
-    assert lib.ts_read_views(None, None, None, 0, None, None, None) == ts.TS_ERR_WORKSPACE
+    assert lib.ts_read_views(None, None, 0, None, 0, None, None, None) == ts.TS_ERR_WORKSPACE
 
 
 def test_accumulation_rule_branches_are_host_logic(lib):

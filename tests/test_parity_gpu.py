@@ -46,6 +46,31 @@ def test_large_batch_bf16_rows():
     _case(w, mode="multi")
 
 
+def test_large_batch_bf16_rows_through_the_single_buffer_entry_point():
+    # the call the benchmark times for this workload: ts_densify_bf16 on the contributions laid end to end
+    w = wl.make("large_batch_bf16")
+    worst, g, r = _case(w, mode="single")
+    assert g["count"].max() > 15000
+
+
+def test_read_views_refuses_arrays_sized_for_fewer_rows():
+    w = wl.make("tiny")
+    ids, rows = w.concatenated()
+    dn = to_dev(w.dense_in)
+    ws = ts.Workspace(w.n_total, w.d, w.V, DEV)
+    try:
+        ts.ts_densify(to_dev(ids), to_dev(rows), w.d, w.V, dn, torch.empty_like(dn))
+        with pytest.raises(ts.TsError) as e:
+            ts.ts_read_views(w.V - 1, w.n_total)          # the last call had V rows
+        assert e.value.status == ts.TS_ERR_CAPACITY
+        with pytest.raises(ts.TsError) as e:
+            ts.ts_read_views(w.V, w.n_total - 1)          # and n_total valid pairs
+        assert e.value.status == ts.TS_ERR_CAPACITY
+        assert ts.ts_read_views(w.V, w.n_total)[3] == w.n_total
+    finally:
+        ws.close()
+
+
 def test_multi_shard_stress_and_buffer_bytes():
     w = wl.make("multi_shard_stress")
     worst, g, r = _case(w, mode="multi", group=2)        # 16 shards of encoder + decoder rows
