@@ -69,6 +69,24 @@ enum { TS_ROW_FP32 = 0, TS_ROW_BF16 = 1 };
 int ts_densify(const int32_t* ids, const float* rows, int64_t n, int32_t d, int32_t V,
                const float* dense_in, float* dense_out, void* stream);
 
+/*
+ * ts_densify for callers that cannot allocate device memory or bind a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels, same bits as ts_densify; the workspace is an array built into
+ * the library's device image, TS_STATIC_SCRATCH_BYTES per GPU, held by every GPU the
+ * library is loaded on until the process ends.  The call allocates and frees nothing and
+ * ignores the bound workspace.  It serves the calls whose workspace fits the array, i.e.
+ * ts_workspace_bytes-many bytes for fp32 rows <= TS_STATIC_SCRATCH_BYTES (V = 32768,
+ * d = 1024: up to about 32 thousand pairs); a larger call returns TS_ERR_CAPACITY before
+ * anything is enqueued.  Every call on a GPU uses that GPU's one array: two such calls that
+ * overlap in time on one GPU (two streams, two threads) race; calls on one stream do not.
+ * Nothing in the array has to survive from call to call, and each call clears what it
+ * needs cleared.  ts_last_views afterwards describes this call.
+ */
+#define TS_STATIC_SCRATCH_BYTES (16 << 20)
+int ts_densify_static(const int32_t* ids, const float* rows, int64_t n, int32_t d, int32_t V,
+                      const float* dense_in, float* dense_out, void* stream);
+
 /* Same as ts_densify, value rows stored as bf16 bit patterns; they are widened exactly and summed in fp32. */
 int ts_densify_bf16(const int32_t* ids, const uint16_t* rows, int64_t n, int32_t d, int32_t V,
                     const float* dense_in, float* dense_out, void* stream);

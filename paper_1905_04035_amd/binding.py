@@ -52,6 +52,7 @@ def lib():
         vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
         l.ts_densify.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
         l.ts_densify_bf16.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
+        l.ts_densify_static.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
         l.ts_densify_multi.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, vp]
         l.ts_densify_scaled.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, i32, C.c_float, vp]
         l.ts_fusion_place.argtypes = [i64, i64, i32, i32, i32, vp, vp]
@@ -73,7 +74,7 @@ def lib():
         l.ts_set_combine_groups.argtypes = [i32]
         l.ts_status_string.argtypes = [C.c_int]
         l.ts_status_string.restype = C.c_char_p
-        for name in ("ts_densify", "ts_densify_bf16", "ts_densify_multi", "ts_buffer_bytes",
+        for name in ("ts_densify", "ts_densify_static", "ts_densify_bf16", "ts_densify_multi", "ts_buffer_bytes",
                      "ts_densify_scaled", "ts_fusion_place", "ts_densify_range",
                      "ts_accumulate_strategy", "ts_accumulate",
                      "ts_workspace_bytes", "ts_bind_workspace", "ts_last_views", "ts_read_views", "ts_unique_ids",
@@ -129,6 +130,18 @@ def ts_densify(ids: torch.Tensor, rows: torch.Tensor, d: int, V: int,
     _check_dense(d, V, dense_in, dense_out)
     _check(lib().ts_densify(_p(ids), _p(rows), ids.numel(), d, V, _p(dense_in), _p(dense_out),
                             _stream(stream)), "ts_densify")
+
+
+TS_STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def ts_densify_static(ids: torch.Tensor, rows: torch.Tensor, d: int, V: int,
+                      dense_in: Optional[torch.Tensor], dense_out: torch.Tensor, stream=None) -> None:
+    """ts_densify on the library's built-in workspace: nothing is allocated or bound."""
+    _check_pair(ids, rows, d, torch.float32)
+    _check_dense(d, V, dense_in, dense_out)
+    _check(lib().ts_densify_static(_p(ids), _p(rows), ids.numel(), d, V, _p(dense_in), _p(dense_out),
+                                   _stream(stream)), "ts_densify_static")
 
 
 def ts_densify_bf16(ids: torch.Tensor, rows: torch.Tensor, d: int, V: int,

@@ -48,6 +48,12 @@
 
 #include "ts_densify.h"
 
+// Built-in workspace of ts_densify_static, the entry point for callers that cannot allocate.
+// One copy per GPU, held from the moment the library is loaded on it until the process
+// ends.  In host code this name is only a handle for hipGetSymbolAddress: kernels and
+// memory calls are given the device address that call returns (static_scratch() below).
+static __device__ __align__(256) unsigned char scratch[TS_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 typedef float f4 __attribute__((ext_vector_type(4)));
@@ -988,6 +994,24 @@ void make_plan(int64_t n, int32_t d, int32_t V, int32_t C, Plan* pl)
 
 int check_hip(hipError_t e) { return e == hipSuccess ? TS_OK : TS_ERR_HIP; }
 
+// Device address of the built-in workspace on the current GPU: every GPU holds its own copy
+// of the array at its own address, looked up once per device and kept.
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return TS_ERR_HIP;
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return TS_ERR_HIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return TS_OK;
+}
+
 // The three kinds of launches, one instantiation per epilogue (the epilogue is a template
 // argument so that the plain path keeps its code).
 template <int EPI>
@@ -1261,6 +1285,23 @@ int ts_densify(const int32_t* ids, const float* rows, int64_t n, int32_t d, int3
 {
     const void* r = rows;
     return densify_shards(&ids, &r, &n, 1, TS_ROW_FP32, d, V, dense_in, dense_out, EPI_NONE, 1.0f, stream);
+}
+
+int ts_densify_static(const int32_t* ids, const float* rows, int64_t n, int32_t d, int32_t V,
+                      const float* dense_in, float* dense_out, void* stream)
+{
+    // the size check comes first: a call that does not fit touches nothing, not even the device
+    if (n < 0 || V <= 0 || d <= 0 || (d % 4) != 0) return TS_ERR_SHAPE;
+    if (n >= ((int64_t)1 << 31)) return TS_ERR_OVERFLOW;
+    Plan pl;
+    make_plan(n, d, V, piece_tokens_for(n, false), &pl);
+    if ((int64_t)pl.total > (int64_t)TS_STATIC_SCRATCH_BYTES) return TS_ERR_CAPACITY;
+    void* ws = nullptr;
+    const int rc = static_scratch(&ws);
+    if (rc != TS_OK) return rc;
+    const void* r = rows;
+    return densify_shards(&ids, &r, &n, 1, TS_ROW_FP32, d, V, dense_in, dense_out, EPI_NONE, 1.0f, stream, 0, -1, ws,
+                          (int64_t)TS_STATIC_SCRATCH_BYTES);
 }
 
 int ts_densify_bf16(const int32_t* ids, const uint16_t* rows, int64_t n, int32_t d, int32_t V,
