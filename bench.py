@@ -57,7 +57,6 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--overlap-mib", type=float, default=-1.0,
                     help="dense bytes copied beside each sort launch (tuning; -1 = library default)")
-    ap.add_argument("--overlap-combine-mib", type=float, default=-1.0, help="tuning; -1 = library default")
     ap.add_argument("--piece-tokens", type=int, default=0, help="tuning; 0 = library default")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run the same launches with n = 0: a plain [V, d] copy of known size, used to "
@@ -88,9 +87,8 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     ts.lib()      # fail loudly if the HIP library has not been built
-    if args.overlap_mib >= 0 or args.overlap_combine_mib >= 0:
-        ts.ts_set_overlap_bytes(int(args.overlap_mib * (1 << 20)) if args.overlap_mib >= 0 else -1,
-                                int(args.overlap_combine_mib * (1 << 20)) if args.overlap_combine_mib >= 0 else -1)
+    if args.overlap_mib >= 0:
+        ts.ts_set_overlap_bytes(int(args.overlap_mib * (1 << 20)))
     if args.piece_tokens:
         ts.ts_set_piece_tokens(args.piece_tokens)
 
@@ -254,7 +252,7 @@ def main():
     alg_reduce = n * elem * d + (4 + out_elem) * d * (whole + untouched_mid)
     roofline = None
     traffic = None
-    default_tuning = (args.overlap_mib < 0 and args.overlap_combine_mib < 0 and not args.piece_tokens and not epilogue)
+    default_tuning = (args.overlap_mib < 0 and not args.piece_tokens and not epilogue)
     if default_tuning and args.workload == COUNTED_TRAFFIC["workload"]:
         import hashlib
         src = os.path.join(ROOT, "paper_1905_04035_amd", "csrc", "ts_densify.hip")

@@ -247,10 +247,10 @@ int ts_read_views(int32_t* count_out, int32_t* row_start_out, int64_t rows_capac
 /*
  * How the most recent call was split over its launches, for byte accounting in
  * benchmarks.  Writes 8 int32 to info (host): [0] piece_tokens C; [1] X: dense rows
- * [0, X) were copied beside the sort launches; [2] T: untouched rows in [X, T) were
- * copied by the row-reduce kernel, those in [T, V) beside the combine launch;
- * [3] sort slices; [4] ids per sort work-group; [5] pieces; [6] combine work-groups per
- * column block; [7] 1 if the call was in place.
+ * [0, X) were copied beside the sort launches; [2] T = V: untouched rows in [X, T) were
+ * copied by the row-reduce kernel; [3] sort slices; [4] ids per sort work-group;
+ * [5] pieces; [6] levels of the tree in which the shares of a cut row are added up;
+ * [7] 1 if the call was in place.
  */
 int ts_last_launch_info(int32_t* info);
 
@@ -279,20 +279,15 @@ int ts_profile_end(float* ms_out, int32_t capacity, int32_t* n_out);
 int ts_set_piece_tokens(int32_t piece_tokens);
 
 /*
- * Tuning.  The sort and the combine launches are latency-bound, so work-groups that copy
- * dense rows run beside them to keep HBM busy.  sort_bytes: dense bytes (read + write)
- * copied from dense_in to dense_out beside each sort launch, before it is known which
- * rows receive pairs (those are overwritten afterwards).  combine_bytes: the same beside
- * the combine launch (untouched rows only).  -1 = default, 0 = none.  Results do not
- * depend on them.
+ * Tuning.  The sort launches are latency-bound, so work-groups that copy dense rows run
+ * beside them to keep HBM busy.  sort_bytes: dense bytes (read + write) copied from dense_in
+ * to dense_out beside each sort launch, before it is known which rows receive pairs (those
+ * are overwritten afterwards).  -1 = default, 0 = none.  Results do not depend on it.
  */
-int ts_set_overlap_bytes(int64_t sort_bytes, int64_t combine_bytes);
+int ts_set_overlap_bytes(int64_t sort_bytes);
 
 /* Tuning.  Ids owned by one sort work-group (64 .. 2048, power of two; 0 = choose from V and n). */
 int ts_set_sort_part(int32_t part);
-
-/* Tuning.  Work-groups per column block that finish cut rows in the combine launch (0 = choose). */
-int ts_set_combine_groups(int32_t groups);
 
 const char* ts_status_string(int status);
 

@@ -69,9 +69,8 @@ def lib():
         l.ts_profile_begin.argtypes = [i32]
         l.ts_profile_end.argtypes = [vp, i32, vp]
         l.ts_set_piece_tokens.argtypes = [i32]
-        l.ts_set_overlap_bytes.argtypes = [i64, i64]
+        l.ts_set_overlap_bytes.argtypes = [i64]
         l.ts_set_sort_part.argtypes = [i32]
-        l.ts_set_combine_groups.argtypes = [i32]
         l.ts_status_string.argtypes = [C.c_int]
         l.ts_status_string.restype = C.c_char_p
         for name in ("ts_densify", "ts_densify_static", "ts_densify_bf16", "ts_densify_multi", "ts_buffer_bytes",
@@ -79,7 +78,7 @@ def lib():
                      "ts_accumulate_strategy", "ts_accumulate",
                      "ts_workspace_bytes", "ts_bind_workspace", "ts_last_views", "ts_read_views", "ts_unique_ids",
                      "ts_last_launch_info",
-                     "ts_profile_begin", "ts_profile_end", "ts_set_piece_tokens", "ts_set_overlap_bytes", "ts_set_sort_part", "ts_set_combine_groups"):
+                     "ts_profile_begin", "ts_profile_end", "ts_set_piece_tokens", "ts_set_overlap_bytes", "ts_set_sort_part"):
             getattr(l, name).restype = C.c_int
         _lib = l
     return _lib
@@ -321,7 +320,7 @@ def ts_last_launch_info() -> dict:
     buf = (C.c_int32 * 8)()
     _check(lib().ts_last_launch_info(buf), "ts_last_launch_info")
     keys = ["piece_tokens", "sort_copy_rows_end", "reduce_copy_rows_end", "sort_slices", "sort_part",
-            "pieces", "combine_groups", "in_place"]
+            "pieces", "combine_levels", "in_place"]
     return dict(zip(keys, list(buf)))
 
 
@@ -340,8 +339,8 @@ def ts_set_piece_tokens(piece_tokens: int) -> None:
     _check(lib().ts_set_piece_tokens(piece_tokens), "ts_set_piece_tokens")
 
 
-def ts_set_overlap_bytes(sort_bytes: int, combine_bytes: int = -1) -> None:
-    _check(lib().ts_set_overlap_bytes(sort_bytes, combine_bytes), "ts_set_overlap_bytes")
+def ts_set_overlap_bytes(sort_bytes: int) -> None:
+    _check(lib().ts_set_overlap_bytes(sort_bytes), "ts_set_overlap_bytes")
 
 
 def ts_set_sort_part(part: int) -> None:

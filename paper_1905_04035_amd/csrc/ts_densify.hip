@@ -82,12 +82,6 @@ constexpr int kSliceTokens = 16384;
 constexpr int kFusedSortMax = 57344;   // up to here one launch sorts everything (measured against two launches)
 constexpr int kPieceSmallMax = 16384;  // up to here pieces of 16 positions, above 32 (bf16 rows read 16 bytes
                                        // per lane: always 16) -- measured
-constexpr int64_t kOverlapCombineBytes = 32ll << 20;   // same for the combine launch
-constexpr int kOneLevelPieces = 1024;  // up to this many pieces the combine is one launch (2048 would be ~2 % faster
-                                       // around 50000 pairs, but a row of 2048 pieces added by 16 wavefronts is a chain
-                                       // of 177 additions: first-order error bound 1.05e-5, above the stated 1e-5)
-constexpr int kSegmentPieces = 256;    // beyond: segments of this many pieces, then a second launch
-constexpr int kCombineGroups = 32;     // work-groups per column block in the combine kernel
 
 // ------------------------------------------------------------------ device helpers
 __device__ __forceinline__ uint64_t ballot64(bool p) { return __ballot(p); }
@@ -169,8 +163,44 @@ struct RowLoad<uint16_t, 2> {
     }
 };
 
-__device__ __forceinline__ f4 load_f4(const float* p) { return *reinterpret_cast<const f4*>(p); }
-__device__ __forceinline__ void store_f4(float* p, f4 v) { *reinterpret_cast<f4*>(p) = v; }
+
+// A partial row that another work-group of the same launch will read: a 16-byte store at
+// agent scope, i.e. written through to memory, so that once it has been acknowledged nothing
+// of it sits dirty in this work-group's L2 slice.  (The compiler offers that scope for
+// 4-byte atomic stores only, and four of those per lane turn every 16-byte store into four
+// strided partial writes; hence the instruction is spelled out.)
+__device__ __forceinline__ void store_f4_through(float* p, f4 v)
+{
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
+}
+
+// The matching load: at agent scope, so it is answered from memory and not from a line that
+// this L2 slice or this compute unit's cache may still hold from an earlier call.  The
+// compiler does not see the load: whoever issues a batch of them waits for the batch with
+// loads_done, which also ties the loaded values to the wait.
+__device__ __forceinline__ f4 load_f4_through(const float* p)
+{
+    f4 v;
+    asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(p) : "memory");
+    return v;
+}
+
+template <int N>
+__device__ __forceinline__ void loads_done(f4 (&x)[N])
+{
+    static_assert(N == 8 || N == 16, "batch sizes of the combine");
+    if constexpr (N == 16)
+        asm volatile("s_waitcnt vmcnt(0)"
+                     : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7]),
+                       "+v"(x[8]), "+v"(x[9]), "+v"(x[10]), "+v"(x[11]), "+v"(x[12]), "+v"(x[13]), "+v"(x[14]), "+v"(x[15])
+                     :
+                     : "memory");
+    else
+        asm volatile("s_waitcnt vmcnt(0)"
+                     : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7])
+                     :
+                     : "memory");
+}
 
 // Streaming accesses for data that is touched once per call (value rows, dense_in,
 // dense_out): the nontemporal hint keeps them from displacing the sort's arrays and the
@@ -214,18 +244,17 @@ __device__ __forceinline__ void store_out(void* out, size_t idx, f4 v, float sca
     }
 }
 
-// One wavefront copies the dense rows v0 .. v0 + R - 1 that lie below vend (with CHECK only
-// those that received no pair): all loads of all rows are issued before the first store.
-template <bool CHECK, int R, int EPI>
-__device__ __forceinline__ void copy_rows(const float* dense_in, void* dense_out, const int32_t* count,
+// One wavefront copies the dense rows v0 .. v0 + R - 1 that lie below vend, except those whose
+// bit is set in `skip` (bit r: row v0 + r): all loads of all rows are issued before the first store.
+template <int R, int EPI>
+__device__ __forceinline__ void copy_rows(const float* dense_in, void* dense_out, uint32_t skip,
                                           int v0, int vend, int d, int lane, float scale)
 {
     bool go[R];
     bool any = false;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        go[r] = v0 + r < vend;
-        if (CHECK && go[r]) go[r] = count[v0 + r] == 0;
+        go[r] = v0 + r < vend && !((skip >> r) & 1u);
         any = any || go[r];
     }
     if (!any) return;
@@ -296,7 +325,8 @@ struct SortParams {
     uint32_t* bad;      // [S]             pairs of the slice with an id outside [0, V)
     int32_t* n_valid;
     int32_t* n_bad;
-    int32_t* n_cut;     // lengths of the two lists of cut rows ([0], [1]), cleared here for the reduce kernel
+    int32_t* arrive;    // arrival counters of the reduce kernel, cleared here (arrive_vec 16-byte words)
+    int32_t arrive_vec;
     // Work-groups past the sorting ones copy dense rows [copy_row0, copy_row1) to the output
     // without knowing yet which rows receive pairs (the reduce kernel, which runs after,
     // overwrites those).  It keeps HBM busy while the latency-bound sort runs.
@@ -396,7 +426,7 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
     if ((int)blockIdx.x >= nsort) {
         const int cw = (int)blockIdx.x - nsort;
         const int v = p.copy_row0 + (cw * kSortWaves + w) * kBigCopyRows;
-        copy_rows<false, kBigCopyRows, EPI>(p.copy_in, p.copy_out, nullptr, v, p.copy_row1, p.d, lane, p.scale);
+        copy_rows<kBigCopyRows, EPI>(p.copy_in, p.copy_out, 0u, v, p.copy_row1, p.d, lane, p.scale);
         return;
     }
     const int g = (int)blockIdx.x % p.G;
@@ -426,6 +456,12 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
 
     int32_t idr[kRoundTiles];
     if (rounds > 0) load_round(sh, j0, j1, ids0, off0, a, b, lane, idr);
+
+    if (MODE != SORT_SCATTER) {
+        // the first launch of a call clears the arrival counters of the reduce kernel
+        u4* const z = reinterpret_cast<u4*>(p.arrive);
+        for (int i = (int)blockIdx.x * 1024 + tid; i < p.arrive_vec; i += nsort * 1024) z[i] = (u4)(0u);
+    }
 
     const size_t GV = (size_t)p.G * part;
     if (MODE == SORT_SCATTER) {
@@ -495,11 +531,7 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
         base = wave_sum(bl);
         nbad = wave_sum(bd);
     }
-    if (MODE != SORT_COUNT && sl == 0 && g == 0 && tid == 0) {
-        *p.n_bad = (int32_t)nbad;
-        p.n_cut[0] = 0;
-        p.n_cut[1] = 0;
-    }
+    if (MODE != SORT_COUNT && sl == 0 && g == 0 && tid == 0) *p.n_bad = (int32_t)nbad;
 
     // The ids of the part, 1024 at a time (thread tid speaks for id lo + i): totals over the
     // wavefronts (and slices), exclusive scan into first positions, running positions per
@@ -640,12 +672,140 @@ struct ReduceParams {
     const float* dense_in;
     void* dense_out;
     float scale;
-    float* partial;             // [2 * pieces][d]
-    int32_t SEG, logC;          // pieces per segment of a cut row (the combine works segment by segment); log2 C
-    int32_t* n_cut;             // [0] segments listed so far, [1] rows of more than one segment
-    int4* cut_list;             // (row id, first piece of the segment, row_start, count), no particular order
-    int4* cut_list2;            // (row id, first piece of the row, row_start, count) of rows of several segments
+    float* partial;             // [2 * pieces][d]: slot 2k holds piece k's share of a row that began earlier,
+                                // slot 2k + 1 its share of a row that begins in it
+    int32_t logC;               // log2 C
+    int32_t* arrive;            // [levels][2 * pieces][ncb] arrival counters, all zero when the launch starts
+    int32_t nslots;             // 2 * pieces
 };
+
+// Fixed-order combine of a row that was cut into pieces, inside the launch that made the
+// pieces.  The shares of a row form a tree with a fan-in of 16: share j of a level belongs
+// to group j / 16, and a group's sum is itself share j / 16 of the next level, until one
+// group holds the whole row.  Every wavefront that has stored a share counts itself in at
+// the share's group; the one that finds all the others there adds the group's shares in a
+// fixed order (a batch at a time as a balanced tree, the batches in order), stores the sum
+// in the slot of the group's first share and moves up a level; at the top dense_in is
+// added and the output row is written.  Which wavefront does the adding depends on timing,
+// what it adds and in which order does not.
+//
+// Ordering without a release fence (which writes the whole L2 back and costs more than the
+// rest of the kernel) and without an acquire fence (which empties this L2 slice for
+// everybody): shares are stored through to memory (store_f4_through); a wavefront counts
+// itself in only after those stores have been acknowledged; the wavefront that sees the
+// full count reads the shares from memory (load_f4_through), past its caches.
+constexpr int kFanIn = 16;
+constexpr int kLogFanIn = 4;
+
+// A share this wavefront has stored: piece k of the cut row `id`, whose c pairs start at
+// sorted position s.
+struct CutRef {
+    int32_t k, id, s, c;
+};
+
+__device__ __forceinline__ size_t share_slot(int k0, int piece_in_row)
+{
+    return piece_in_row == 0 ? (size_t)(2 * k0 + 1) : (size_t)2 * (size_t)(k0 + piece_in_row);
+}
+
+__device__ __forceinline__ int32_t* arrival_counter(const ReduceParams& p, int level, size_t first_slot, int cb)
+{
+    return p.arrive + ((size_t)level * p.nslots + first_slot) * p.ncb + cb;
+}
+
+// Counts a level-0 share in.  The caller has made sure that the share's stores are
+// acknowledged.  Returns (in lane 0) how many shares of the group had arrived before.
+__device__ __forceinline__ int announce_share(const ReduceParams& p, const CutRef& r, int cb, int lane)
+{
+    const int k0 = r.s >> p.logC;
+    const int g = (r.k - k0) >> kLogFanIn;
+    int arrived = 0;
+    if (lane == 0)
+        arrived = __hip_atomic_fetch_add(arrival_counter(p, 0, share_slot(k0, g << kLogFanIn), cb), 1, __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT);
+    return arrived;
+}
+
+// arrived0: what announce_share returned for this share.  If the share was its group's
+// last, adds the group up and climbs the tree for as long as it is the last to arrive.
+template <int NV, int EPI>
+__device__ __forceinline__ void combine_if_last(const ReduceParams& p, const CutRef& r, int cb, int col, bool colok,
+                                                int lane, int arrived0)
+{
+    constexpr int kBatch = 16 / NV;                 // shares loaded together
+    const int k0 = r.s >> p.logC;                                     // the row's first piece
+    int Pl = ((r.s + r.c - 1) >> p.logC) - k0 + 1;                    // shares at this level (pieces at level 0)
+    int j = r.k - k0;                                                 // this wavefront's share
+    int shift = 0;                                                    // a share of this level spans 16^level pieces
+    int arrived = __builtin_amdgcn_readfirstlane(arrived0);
+    for (int level = 0;; ++level) {
+        const int g = j >> kLogFanIn;
+        const int m = min(kFanIn, Pl - (g << kLogFanIn));             // shares in this group
+        const size_t first_slot = share_slot(k0, (g << kLogFanIn) << shift);
+        const bool top = Pl <= kFanIn;
+        if (level > 0) {
+            // the group sum stored below has to be in memory before it is counted in
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            int x = 0;
+            if (lane == 0)
+                x = __hip_atomic_fetch_add(arrival_counter(p, level, first_slot, cb), 1, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
+            arrived = __builtin_amdgcn_readfirstlane(x);
+        }
+        if (arrived != m - 1) return;
+        f4 dn[NV];
+#pragma unroll
+        for (int q = 0; q < NV; ++q) {
+            dn[q] = (f4)(0.0f);
+            if (top && colok && p.dense_in) dn[q] = load_f4_stream(p.dense_in + (size_t)r.id * p.d + col + 4 * q);
+        }
+        f4 tot[NV];
+#pragma unroll
+        for (int q = 0; q < NV; ++q) tot[q] = (f4)(0.0f);
+        for (int i0 = 0; i0 < m; i0 += kBatch) {
+            f4 x[kBatch * NV];          // share u of the batch, vector q: x[u * NV + q]
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {
+                const int i = i0 + u;
+                const size_t sl = share_slot(k0, ((g << kLogFanIn) + min(i, m - 1)) << shift);
+#pragma unroll
+                for (int q = 0; q < NV; ++q) {
+                    x[u * NV + q] = (f4)(0.0f);
+                    if (i < m && colok) x[u * NV + q] = load_f4_through(p.partial + sl * p.d + col + 4 * q);
+                }
+            }
+            loads_done(x);
+#pragma unroll
+            for (int w = 1; w < kBatch; w <<= 1)
+#pragma unroll
+                for (int u = 0; u + w < kBatch; u += 2 * w)
+#pragma unroll
+                    for (int q = 0; q < NV; ++q) x[u * NV + q] += x[(u + w) * NV + q];
+#pragma unroll
+            for (int q = 0; q < NV; ++q) tot[q] += x[q];
+        }
+        if (top) {
+            if (colok) {
+#pragma unroll
+                for (int q = 0; q < NV; ++q) {
+                    if constexpr (EPI == EPI_NONE)
+                        store_f4_stream(reinterpret_cast<float*>(p.dense_out) + (size_t)r.id * p.d + col + 4 * q,
+                                        tot[q] + dn[q]);
+                    else
+                        store_out<EPI>(p.dense_out, (size_t)r.id * p.d + col + 4 * q, tot[q] + dn[q], p.scale);
+                }
+            }
+            return;
+        }
+        if (colok) {
+#pragma unroll
+            for (int q = 0; q < NV; ++q) store_f4_through(p.partial + first_slot * p.d + col + 4 * q, tot[q]);
+        }
+        j = g;
+        Pl = (Pl + kFanIn - 1) >> kLogFanIn;
+        shift += kLogFanIn;
+    }
+}
 
 // NV: 16-byte fp32 vectors per lane (a wavefront item covers 256 * NV columns); BATCH: sorted
 // positions whose rows are loaded together.
@@ -659,7 +819,8 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
     if (item >= p.n_piece_items) {
         // ---- copy item: one output row, copied if it received no pair
         const int v = p.copy_row0 + item - p.n_piece_items;
-        copy_rows<true, 1, EPI>(p.dense_in, p.dense_out, p.count, v, p.copy_row1, p.d, lane, p.scale);
+        const uint32_t skip = (v < p.copy_row1 && p.count[v] != 0) ? 1u : 0u;
+        copy_rows<1, EPI>(p.dense_in, p.dense_out, skip, v, p.copy_row1, p.d, lane, p.scale);
         return;
     }
 
@@ -699,22 +860,6 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
     const uint64_t Lm = ballot64(last);
     const uint64_t W = ballot64(whole);
     if (A == 0) return;
-    // A cut row is announced segment by segment (SEG pieces each), by the item that holds the
-    // segment's first piece: the lane of the row's first pair, or lane 0 for a later segment.
-    // A row of several segments is also put on the second list, once.
-    if (cb == 0 && active && !whole) {
-        const int k0 = s >> p.logC;          // C and SEG are powers of two
-        const bool row_first = wpos == s;
-        const bool seg_first = lane == 0 && s < pos0 && ((k - k0) & (p.SEG - 1)) == 0;
-        if (row_first || seg_first) {
-            const int e = atomicAdd(&p.n_cut[0], 1);
-            p.cut_list[e] = make_int4(id, k, s, c);
-        }
-        if (row_first && ((s + c - 1) >> p.logC) - k0 + 1 > p.SEG) {
-            const int e = atomicAdd(&p.n_cut[1], 1);
-            p.cut_list2[e] = make_int4(id, k0, s, c);
-        }
-    }
     const int a = __builtin_ctzll(A);
     const int b = 64 - __builtin_clzll(A);
     const uint32_t slot = (uint32_t)(2 * k + (s >= pos0 ? 1 : 0));
@@ -770,108 +915,40 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
                         if (colok) {
 #pragma unroll
                             for (int q = 0; q < NV; ++q)
-                                store_f4(p.partial + (size_t)sj * p.d + col + 4 * q, acc[q]);
+                                store_f4_through(p.partial + (size_t)sj * p.d + col + 4 * q, acc[q]);
                         }
                     }
                 }
             }
         }
     }
-}
 
-// ------------------------------------------------------------------ combine
-struct CombineParams {
-    int32_t V, d, C, ncb;
-    const int32_t* count;
-    int32_t SEG, logSEG, logC;  // pieces per segment; log2 of it and of C
-    int32_t level;              // 1: add the pieces of a segment; 2: add the segment sums of a row
-    const int32_t* n_cut;       // the list's length
-    const int4* cut_list;
-    const float* dense_in;
-    void* dense_out;
-    float scale;
-    float* partial;
-    int32_t groups;             // combining work-groups per column block
-    int32_t copy_row0, copy_row1;   // untouched rows copied by the work-groups past the combining ones
-};
-
-// Work-group (e, cb) handles column block cb of the list entries e, e + groups, ...
-// Level 1: an entry is a segment of at most SEG pieces of a cut row.  Its partial rows are
-// split into 16 contiguous shares, one per wavefront, each added in piece order; wavefront 0
-// then adds the shares in order.  If the row has no other segment, dense_in is added and the
-// row is written; otherwise the segment's sum replaces the partial row of its first piece.
-// Level 2 (only launched when rows can have several segments): an entry is such a row; the
-// same walk over its segment sums, dense_in added last, row written.
-template <int EPI>
-__global__ __launch_bounds__(1024, 8) void combine_kernel(CombineParams p)
-{
-    __shared__ f4 share[kSortWaves][64];
-
-    const int lane = threadIdx.x & 63;
-    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int ncombine = p.groups * p.ncb;
-    if ((int)blockIdx.x >= ncombine) {
-        const int v = p.copy_row0 + (((int)blockIdx.x - ncombine) * kSortWaves + w) * kBigCopyRows;
-        copy_rows<true, kBigCopyRows, EPI>(p.dense_in, p.dense_out, p.count, v, p.copy_row1, p.d, lane, p.scale);
-        return;
-    }
-    const int cb = (int)blockIdx.x % p.ncb;
-    const int e0 = (int)blockIdx.x / p.ncb;
-    int4 ent = p.cut_list[e0];          // read beside n_cut; meaningless when e0 >= n_cut
-    const int ncut = *p.n_cut;
-    const int col = cb * kColBlock + lane * 4;
-    const bool colok = col < p.d;
-
-    for (int e = e0; e < ncut; e += p.groups) {
-        if (e != e0) ent = p.cut_list[e];
-        const int v = ent.x;
-        const int k0 = ent.z >> p.logC;                              // the row's first piece
-        const int Prow = ((ent.z + ent.w - 1) >> p.logC) - k0 + 1;  // the row's pieces, >= 2
-        const int k = ent.y;                                         // first piece summed here
-        const int stride = p.level == 1 ? 1 : p.SEG;
-        const int P = p.level == 1 ? min(p.SEG, Prow - (k - k0)) : (Prow + p.SEG - 1) >> p.logSEG;
-        const bool final = p.level == 2 || Prow <= p.SEG;
-        f4 dn = (f4)(0.0f);
-        if (final && w == 0 && colok && p.dense_in) dn = load_f4_stream(p.dense_in + (size_t)v * p.d + col);
-        const int per = (P + kSortWaves - 1) / kSortWaves;
-        const int j0 = min(P, w * per);
-        const int j1 = min(P, j0 + per);
-
-        f4 acc = (f4)(0.0f);
-        for (int jb = j0; jb < j1; jb += 8) {
-            f4 x[8];
+    // The shares of cut rows that this item has left in scratch (at most two cut rows pass
+    // through a piece: one that ends in it, one that begins in it) are counted in once their
+    // stores are acknowledged; whoever brings a group's last share adds the group up.
+    uint64_t cuts = Lm & ~W & A;
+    if (cuts == 0) return;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    CutRef ref[2];
+    int answer[2];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int j = jb + u;
-                x[u] = (f4)(0.0f);
-                if (j < j1 && colok) {
-                    const int kb = k + j * stride;
-                    const size_t sl = (kb == k0) ? (size_t)(2 * kb + 1) : (size_t)(2 * kb);
-                    x[u] = load_f4(p.partial + sl * p.d + col);
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-                if (jb + u < j1) acc += x[u];
+    for (int q = 0; q < 2; ++q) {
+        answer[q] = 0;
+        if (cuts) {
+            const int j = __builtin_ctzll(cuts);
+            ref[q].k = k;
+            ref[q].id = (int)bcast((uint32_t)id, j);
+            ref[q].s = (int)bcast((uint32_t)s, j);
+            ref[q].c = (int)bcast((uint32_t)c, j);
+            answer[q] = announce_share(p, ref[q], cb, lane);
+        } else {
+            ref[q].k = -1;
         }
-        share[w][lane] = acc;
-        __syncthreads();
-        if (w == 0 && colok) {
-            f4 tot = share[0][lane];
-            for (int q = 1; q < kSortWaves; ++q)
-                if (q * per < P) tot += share[q][lane];
-            if (final) {
-                if constexpr (EPI == EPI_NONE)
-                    store_f4_stream(reinterpret_cast<float*>(p.dense_out) + (size_t)v * p.d + col, tot + dn);
-                else
-                    store_out<EPI>(p.dense_out, (size_t)v * p.d + col, tot + dn, p.scale);
-            } else {
-                const size_t sl = (k == k0) ? (size_t)(2 * k + 1) : (size_t)(2 * k);
-                store_f4(p.partial + sl * p.d + col, tot);
-            }
-        }
-        __syncthreads();
+        cuts &= cuts - 1;
     }
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+        if (ref[q].k >= 0) combine_if_last<NV, EPI>(p, ref[q], cb, col, colok, lane, answer[q]);
 }
 
 // ------------------------------------------------------------------ unique ids (introspection)
@@ -903,16 +980,14 @@ __global__ __launch_bounds__(1024) void unique_kernel(const int32_t* count, int 
 
 // ------------------------------------------------------------------ host side
 struct Plan {
-    int32_t S, SL, G, part, C, NB, SEG, ncb;   // ncb: 256-column blocks of a row
-    size_t off_nvalid, off_nbad, off_ncut, off_cut_list, off_cut_list2, off_count, off_row_start, off_sorted, off_tot,
+    int32_t S, SL, G, part, list_cap, C, NB, levels, ncb;   // ncb: 256-column blocks of a row; levels of the combine tree
+    size_t off_nvalid, off_nbad, off_arrive, arrive_bytes, off_count, off_row_start, off_sorted, off_tot,
         off_below, off_bad, off_partial, total;
 };
 
 int g_piece_override = 0;
 int64_t g_overlap_sort = -1;            // dense bytes (read + write) copied beside each sort launch; -1 = default
-int64_t g_overlap_combine = -1;         // same, beside the combine launch
 int32_t g_part_override = 0;
-int32_t g_combine_groups = 0;           // 0 = choose from the number of pieces
 void* g_ws = nullptr;
 int64_t g_ws_bytes = 0;
 Plan g_last_plan;
@@ -959,22 +1034,23 @@ void make_plan(int64_t n, int32_t d, int32_t V, int32_t C, Plan* pl)
     while (pl->S == 1 && part > kMinPart && (int64_t)((V + part - 1) / part) < 64) part >>= 1;
     if (g_part_override) part = g_part_override;
     pl->part = part;
+    // a list that holds a whole round never has to be rebuilt; parts of 2048 ids leave room
+    // for short lists only
+    pl->list_cap = part <= 1024 ? kRoundPairs : kListCap;
     pl->G = (V + part - 1) / part;
     pl->C = C;
     pl->NB = (int32_t)((n + pl->C - 1) / pl->C);
-    // the combine adds a cut row's partial rows in segments; with few pieces one segment holds
-    // any row and a single combine launch does
-    pl->SEG = pl->NB <= kOneLevelPieces ? (1 << 30) : kSegmentPieces;     // powers of two
+    // a cut row's shares are added up in a tree with a fan-in of 16: levels needed for a row of NB pieces
+    pl->levels = 1;
+    for (int64_t reach = kFanIn; reach < pl->NB; reach *= kFanIn) ++pl->levels;
     pl->ncb = (d + kColBlock - 1) / kColBlock;
     size_t o = 0;
     pl->off_nvalid = o;
     pl->off_nbad = o + 4;
-    pl->off_ncut = o + 8;
     o = 256;
-    pl->off_cut_list = o;
-    o = align_up(o + (size_t)2 * pl->NB * 16, 256);
-    pl->off_cut_list2 = o;
-    o = align_up(o + ((size_t)pl->NB / pl->SEG + 2) * 16, 256);
+    pl->off_arrive = o;
+    pl->arrive_bytes = align_up((size_t)pl->levels * 2 * pl->NB * pl->ncb * 4, 256);
+    o += pl->arrive_bytes;
     pl->off_count = o;
     o = align_up(o + (size_t)V * 4, 256);
     pl->off_row_start = o;
@@ -1044,12 +1120,6 @@ void launch_reduce(unsigned grid, bool wide, int32_t row_dtype, hipStream_t stre
         launch_timed(reduce_kernel<float, 1, 8, EPI>, grid, stream, begin, end, rp);
 }
 
-template <int EPI>
-void launch_combine(unsigned grid, hipStream_t stream, const CombineParams& cp)
-{
-    hipLaunchKernelGGL(combine_kernel<EPI>, dim3(grid), dim3(1024), 0, stream, cp);
-}
-
 #define TS_DISPATCH_EPI(epi, fn, ...)                              \
     do {                                                           \
         if ((epi) == EPI_NONE) fn<EPI_NONE>(__VA_ARGS__);          \
@@ -1088,7 +1158,8 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     sp.bad = (uint32_t*)(ws + pl.off_bad);
     sp.n_valid = (int32_t*)(ws + pl.off_nvalid);
     sp.n_bad = (int32_t*)(ws + pl.off_nbad);
-    sp.n_cut = (int32_t*)(ws + pl.off_ncut);
+    sp.arrive = (int32_t*)(ws + pl.off_arrive);
+    sp.arrive_vec = (int32_t)(pl.arrive_bytes / 16);
 
     // In place, the plain path leaves untouched rows alone.  With an epilogue they still have
     // to be scaled, by the item that reads them; only the copy made before the pairs are
@@ -1100,9 +1171,9 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     // per 1024 pairs beyond (the wavefronts then walk their shares in several rounds).  A sort
     // of a few slices leaves compute units idle, and a smaller blind copy beside
     // each of its two launches still pays (+4 % at 3-4 slices); a sort of many slices keeps the
-    // whole GPU busy by itself, and with that many pairs a large share of the rows copied
-    // blindly would be overwritten: no blind copy then.
-    const int64_t sixteenths = n * 16 / 16384;
+    // whole GPU busy by itself (a copying work-group beside every sorting one lengthens the sort
+    // by more than the copy is worth), and with that many pairs a large share of the rows
+    // copied blindly would be overwritten: no blind copy then.
     const int64_t budget_single = n <= 16384 ? (32ll << 20) + (n / 1024 << 20)
                                              : (48ll << 20) + (n - 16384) / 1024 * (5ll << 19);
     const int64_t budget_multi = pl.S <= 4 ? (32ll << 20) : (pl.S <= 6 ? (16ll << 20) : 0);
@@ -1110,16 +1181,7 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
                                                : (pl.S == 1 ? budget_single : budget_multi);
     int64_t rows_per_launch = (in_place || (pl.S > 1 && epi != EPI_NONE)) ? 0 : budget / ((int64_t)8 * d);
     rows_per_launch = rows_per_launch / (kBigCopyRows * kSortWaves) * (kBigCopyRows * kSortWaves);
-    // rows copied by the combine launch, taken from the end
-    // (with many pairs most rows receive some and the combine has many more entries to walk: a
-    // small copy measured best)
-    const int64_t budget_c = g_overlap_combine >= 0 ? g_overlap_combine
-                             : (pl.S > 1 || n > 32768) ? (4ll << 20)
-                                                    : kOverlapCombineBytes * (16 + (sixteenths < 16 ? sixteenths : 16)) / 32;
-    int64_t rows_tail = (skip_untouched || pl.NB == 0) ? 0 : budget_c / ((int64_t)8 * d);
-    rows_tail = rows_tail / (kBigCopyRows * kSortWaves) * (kBigCopyRows * kSortWaves);
-    if (rows_tail > V) rows_tail = V;
-    const int32_t tail0 = (int32_t)(V - rows_tail);
+    const int32_t tail0 = V;
     int32_t copy_done = 0;
     auto sort_grid = [&](SortParams& q) {
         q.copy_row0 = copy_done;
@@ -1131,9 +1193,7 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     sp.copy_out = dense_out;
     sp.d = d;
     sp.scale = scale;
-    // a list that holds a whole round never has to be rebuilt; parts of 2048 ids leave room
-    // for short lists only
-    sp.list_cap = pl.part <= 1024 ? kRoundPairs : kListCap;
+    sp.list_cap = pl.list_cap;
     const size_t lds = ((size_t)(kSortWaves + 2) * pl.part + (size_t)kSortWaves * sp.list_cap) * sizeof(uint32_t);
     if (pl.S == 1) {
         const dim3 g1 = sort_grid(sp);
@@ -1160,10 +1220,8 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     rp.dense_out = dense_out;
     rp.scale = scale;
     rp.partial = (float*)(ws + pl.off_partial);
-    rp.n_cut = sp.n_cut;
-    rp.cut_list = (int4*)(ws + pl.off_cut_list);
-    rp.cut_list2 = (int4*)(ws + pl.off_cut_list2);
-    rp.SEG = pl.SEG;
+    rp.arrive = sp.arrive;
+    rp.nslots = 2 * pl.NB;
     rp.logC = __builtin_ctz((unsigned)pl.C);
     rp.copy_row0 = copy_done;
     rp.copy_row1 = tail0;
@@ -1177,40 +1235,6 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     if (prof) ++g_prof_used;
     if (hipGetLastError() != hipSuccess) return TS_ERR_HIP;
 
-    if (pl.NB > 0) {
-        CombineParams cp;
-        cp.V = V;
-        cp.d = d;
-        cp.C = pl.C;
-        cp.ncb = pl.ncb;
-        cp.count = sp.count;
-        cp.SEG = pl.SEG;
-        cp.logSEG = __builtin_ctz((unsigned)pl.SEG);
-        cp.logC = __builtin_ctz((unsigned)pl.C);
-        cp.level = 1;
-        cp.n_cut = sp.n_cut;
-        cp.cut_list = rp.cut_list;
-        cp.dense_in = dense_in;
-        cp.dense_out = dense_out;
-        cp.scale = scale;
-        cp.partial = rp.partial;
-        const int want = g_combine_groups ? g_combine_groups : (pl.NB <= 1024 ? kCombineGroups : 4 * kCombineGroups);
-        cp.groups = pl.NB < want ? pl.NB : want;
-        cp.copy_row0 = tail0;
-        cp.copy_row1 = V;
-        const unsigned cgrid = (unsigned)(cp.groups * pl.ncb + (V - tail0 + kBigCopyRows * kSortWaves - 1) / (kBigCopyRows * kSortWaves));
-        TS_DISPATCH_EPI(epi, launch_combine, cgrid, stream, cp);
-        if (pl.NB > pl.SEG) {
-            // rows of several segments: add their segment sums
-            cp.level = 2;
-            cp.n_cut = sp.n_cut + 1;
-            cp.cut_list = rp.cut_list2;
-            cp.groups = pl.NB / pl.SEG + 1 < 64 ? pl.NB / pl.SEG + 1 : 64;
-            cp.copy_row0 = cp.copy_row1 = V;
-            TS_DISPATCH_EPI(epi, launch_combine, (unsigned)(cp.groups * pl.ncb), stream, cp);
-        }
-        if (hipGetLastError() != hipSuccess) return TS_ERR_HIP;
-    }
     g_last_plan = pl;
     g_last_ws = ws_v;
     g_last_V = V;
@@ -1220,7 +1244,7 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     g_last_info[3] = pl.S;
     g_last_info[4] = pl.part;
     g_last_info[5] = pl.NB;
-    g_last_info[6] = g_combine_groups;
+    g_last_info[6] = pl.levels;
     g_last_info[7] = in_place ? 1 : 0;
     g_have_last = true;
     return TS_OK;
@@ -1488,26 +1512,18 @@ int ts_profile_end(float* ms_out, int32_t capacity, int32_t* n_out)
     return TS_OK;
 }
 
-int ts_set_overlap_bytes(int64_t sort_bytes, int64_t combine_bytes)
+int ts_set_overlap_bytes(int64_t sort_bytes)
 {
-    if (sort_bytes < -1 || combine_bytes < -1) return TS_ERR_SHAPE;
+    if (sort_bytes < -1) return TS_ERR_SHAPE;
     g_overlap_sort = sort_bytes;
-    g_overlap_combine = combine_bytes;
     return TS_OK;
 }
 
 int ts_set_sort_part(int32_t part)
 {
-    if (part != 0 && part != 64 && part != 128 && part != 256 && part != 512 && part != 1024 && part != 2048)
+    if (part != 0 && part != 64 && part != 128 && part != 256 && part != 512 && part != 1024 && part != kMaxPart)
         return TS_ERR_SHAPE;
     g_part_override = part;
-    return TS_OK;
-}
-
-int ts_set_combine_groups(int32_t groups)
-{
-    if (groups < 0 || groups > 65535) return TS_ERR_SHAPE;
-    g_combine_groups = groups;
     return TS_OK;
 }
 

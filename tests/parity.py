@@ -9,9 +9,9 @@ from paper_1905_04035_amd import workloads as wl
 
 # fp32 outputs must satisfy |gpu - exact| <= TOL * (sum of |terms| of that element).
 # The library adds at most C <= 32 rows in sequence inside a piece, then the pieces of a
-# cut row in 16 contiguous shares, the shares in sequence, and dense_in last; with fp32
-# unit round-off 2^-24 the first-order bound is (depth - 1) * 2^-24 * sum|terms|, below 1e-5
-# for every case tested here (see error_depth and error_bound below).
+# cut row in a tree with a fan-in of 16, and dense_in last; with fp32 unit round-off 2^-24
+# the first-order bound is (depth - 1) * 2^-24 * sum|terms|, below 1e-5 for any row of
+# fewer than 16^8 pieces (see error_depth and error_bound below).
 TOL = 1e-5
 DEV = "cuda:0"
 
@@ -94,20 +94,21 @@ def check(g, r: oracle.OracleResult, w: wl.Workload, exact_bits=False):
     return float(np.max(err / scale))
 
 
-def error_depth(count_max: int, C: int, pieces_in_call: int) -> int:
-    """Additions on the longest chain a term of the fullest row can take: C inside a piece; the
-    pieces of a wavefront's share (16 shares), the shares, dense_in.  With more than 1024 pieces
-    in the call a row is combined in segments of 256 pieces first, then the segment sums the
-    same way."""
-    P = -(-count_max // C) + 1
+def error_depth(count_max: int, C: int) -> int:
+    """Additions on the longest chain a term of the fullest row can take: C inside a piece; then,
+    per level of the tree in which the shares of a cut row are added up (fan-in 16: one level up
+    to 16 pieces, two up to 256, ...), a balanced tree over a batch of shares followed by the
+    batches in sequence: 4 + 1 for one batch of 16 (fp32 rows), 3 + 2 for two batches of 8 (bf16
+    rows read 16 bytes per lane); dense_in last."""
     if count_max <= C:
         return count_max + 1
-    if pieces_in_call <= 1024:
-        return C + -(-P // 16) + 16 + 1
-    segments = -(-P // 256) + 1
-    return C + 16 + 16 + -(-segments // 16) + 16 + 1
+    P = -(-count_max // C) + 1
+    levels = 1
+    while 16 ** levels < P:
+        levels += 1
+    return C + 5 * levels + 1
 
 
-def error_bound(count_max: int, C: int, pieces_in_call: int) -> float:
+def error_bound(count_max: int, C: int) -> float:
     """First-order bound on |err| / sum|terms| for fp32 sums in that order."""
-    return (error_depth(count_max, C, pieces_in_call) - 1) * 2.0 ** -24
+    return (error_depth(count_max, C) - 1) * 2.0 ** -24

@@ -177,10 +177,8 @@ def test_tuning_setters_validate(lib):
     assert lib.ts_set_piece_tokens(0) == ts.TS_OK
     assert lib.ts_set_sort_part(100) == ts.TS_ERR_SHAPE
     assert lib.ts_set_sort_part(0) == ts.TS_OK
-    assert lib.ts_set_overlap_bytes(-2, 0) == ts.TS_ERR_SHAPE
-    assert lib.ts_set_overlap_bytes(-1, -1) == ts.TS_OK
-    assert lib.ts_set_combine_groups(-1) == ts.TS_ERR_SHAPE
-    assert lib.ts_set_combine_groups(0) == ts.TS_OK
+    assert lib.ts_set_overlap_bytes(-2) == ts.TS_ERR_SHAPE
+    assert lib.ts_set_overlap_bytes(-1) == ts.TS_OK
 
 
 def test_status_strings(lib):

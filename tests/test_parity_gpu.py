@@ -190,7 +190,7 @@ def test_sort_part_sizes_and_lists_of_owned_pairs(part, ids):
 def test_result_does_not_depend_on_the_overlapped_copy(mib):
     w = wl.make_custom(V=5000, d=512, n_list=[6000, 3000], seed=46)
     ref = run_gpu(w, mode="multi")
-    ts.ts_set_overlap_bytes(mib << 20, (mib // 2) << 20)
+    ts.ts_set_overlap_bytes(mib << 20)
     try:
         _case(w, mode="multi")
         got = run_gpu(w, mode="multi")
@@ -198,7 +198,7 @@ def test_result_does_not_depend_on_the_overlapped_copy(mib):
         wb = wl.make_custom(V=3000, d=256, n_list=[70000], seed=47)      # two sort launches
         _case(wb)
     finally:
-        ts.ts_set_overlap_bytes(-1, -1)
+        ts.ts_set_overlap_bytes(-1)
     assert np.array_equal(ref["out"].view(np.uint32), got["out"].view(np.uint32))
 
 
@@ -375,7 +375,7 @@ def test_measured_error_stays_under_the_a_priori_bound(name, group):
     # exceed the first-order bound for its longest chain, which itself lies under the tolerance
     w = wl.make(name)
     worst, g, r = _case(w, mode="multi", group=group)
-    bound = error_bound(int(r.count.max()), g["info"]["piece_tokens"], g["info"]["pieces"])
+    bound = error_bound(int(r.count.max()), g["info"]["piece_tokens"])
     assert bound < TOL
     assert worst <= bound, (worst, bound)
 
