@@ -241,15 +241,13 @@ def main():
     count = ts.ts_read_views(V, n)[0].numpy()
 
     # Algorithmic bytes of one launch of the row-reduce kernel: every value row once; dense_in
-    # read and dense_out written for each output row it finishes itself (1..C pairs) and for
-    # each untouched row of the range it copies.  Rows cut into pieces (more than C pairs) get
-    # their dense traffic in the combine kernel; the other untouched rows are copied beside the
-    # sort and the combine launches; ids are read by the sort.
-    C = info["piece_tokens"]
+    # read and dense_out written for every output row that received pairs (all of them are
+    # finished in this launch) and for each untouched row of the range it copies.  The other
+    # untouched rows are copied beside the sort launches; ids are read by the sort.
     x0, x1 = info["sort_copy_rows_end"], info["reduce_copy_rows_end"]
-    whole = int(((count > 0) & (count <= C)).sum())
+    touched = int((count > 0).sum())
     untouched_mid = int((count[x0:x1] == 0).sum())
-    alg_reduce = n * elem * d + (4 + out_elem) * d * (whole + untouched_mid)
+    alg_reduce = n * elem * d + (4 + out_elem) * d * (touched + untouched_mid)
     roofline = None
     traffic = None
     default_tuning = (args.overlap_mib < 0 and not args.piece_tokens and not epilogue)

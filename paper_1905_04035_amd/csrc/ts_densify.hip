@@ -663,8 +663,8 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
 // ------------------------------------------------------------------ reduce
 struct ReduceParams {
     int32_t V, d, C, ncb;
-    int32_t n_piece_items;      // pieces x column blocks
-    int32_t copy_row0, copy_row1;   // copy items cover the untouched rows in this range
+    int32_t n_piece_groups;     // work-groups that sum pieces: (groups of kGroupPieces pieces) x column blocks
+    int32_t copy_row0, copy_row1;   // the work-groups after them copy the untouched rows in this range
     const int32_t* count;
     const SortedPair* sorted;
     int32_t n;                  // pairs in the call (records beyond n_valid hold nothing)
@@ -672,15 +672,19 @@ struct ReduceParams {
     const float* dense_in;
     void* dense_out;
     float scale;
-    float* partial;             // [2 * pieces][d]: slot 2k holds piece k's share of a row that began earlier,
-                                // slot 2k + 1 its share of a row that begins in it
-    int32_t logC;               // log2 C
-    int32_t* arrive;            // [levels][2 * pieces][ncb] arrival counters, all zero when the launch starts
-    int32_t nslots;             // 2 * pieces
+    float* partial;             // [2 * groups][d]: slot 2g holds group g's share of a row that began before it,
+                                // slot 2g + 1 its share of a row that begins in it and goes on beyond it
+    int32_t logC, logG;         // log2 C; log2 of the sorted positions of a group of pieces
+    int32_t* arrive;            // [levels][2 * groups][ncb] arrival counters, all zero when the launch starts
+    int32_t nslots;             // 2 * groups
 };
 
-// Fixed-order combine of a row that was cut into pieces, inside the launch that made the
-// pieces.  The shares of a row form a tree with a fan-in of 16: share j of a level belongs
+constexpr int kGroupPieces = 4;     // pieces per work-group of the reduce kernel, one per wavefront
+constexpr int kLogGroupPieces = 2;
+
+// Fixed-order combine of a row that spans several work-groups, inside the launch that made
+// the shares (a share: what one work-group's pieces hold of the row, already added up in
+// piece order).  The shares of a row form a tree with a fan-in of 16: share j of a level belongs
 // to group j / 16, and a group's sum is itself share j / 16 of the next level, until one
 // group holds the whole row.  Every wavefront that has stored a share counts itself in at
 // the share's group; the one that finds all the others there adds the group's shares in a
@@ -697,15 +701,16 @@ struct ReduceParams {
 constexpr int kFanIn = 16;
 constexpr int kLogFanIn = 4;
 
-// A share this wavefront has stored: piece k of the cut row `id`, whose c pairs start at
-// sorted position s.
+// A share this wavefront has stored: that of group k (of pieces) of the cut row `id`, whose
+// c pairs start at sorted position s.
 struct CutRef {
     int32_t k, id, s, c;
 };
 
-__device__ __forceinline__ size_t share_slot(int k0, int piece_in_row)
+// k0: the group in which the row begins.
+__device__ __forceinline__ size_t share_slot(int k0, int group_in_row)
 {
-    return piece_in_row == 0 ? (size_t)(2 * k0 + 1) : (size_t)2 * (size_t)(k0 + piece_in_row);
+    return group_in_row == 0 ? (size_t)(2 * k0 + 1) : (size_t)2 * (size_t)(k0 + group_in_row);
 }
 
 __device__ __forceinline__ int32_t* arrival_counter(const ReduceParams& p, int level, size_t first_slot, int cb)
@@ -717,7 +722,7 @@ __device__ __forceinline__ int32_t* arrival_counter(const ReduceParams& p, int l
 // acknowledged.  Returns (in lane 0) how many shares of the group had arrived before.
 __device__ __forceinline__ int announce_share(const ReduceParams& p, const CutRef& r, int cb, int lane)
 {
-    const int k0 = r.s >> p.logC;
+    const int k0 = r.s >> p.logG;
     const int g = (r.k - k0) >> kLogFanIn;
     int arrived = 0;
     if (lane == 0)
@@ -733,10 +738,10 @@ __device__ __forceinline__ void combine_if_last(const ReduceParams& p, const Cut
                                                 int lane, int arrived0)
 {
     constexpr int kBatch = 16 / NV;                 // shares loaded together
-    const int k0 = r.s >> p.logC;                                     // the row's first piece
-    int Pl = ((r.s + r.c - 1) >> p.logC) - k0 + 1;                    // shares at this level (pieces at level 0)
+    const int k0 = r.s >> p.logG;                                     // the row's first group of pieces
+    int Pl = ((r.s + r.c - 1) >> p.logG) - k0 + 1;                    // shares at this level (groups at level 0)
     int j = r.k - k0;                                                 // this wavefront's share
-    int shift = 0;                                                    // a share of this level spans 16^level pieces
+    int shift = 0;                                                    // a share of this level spans 16^level groups
     int arrived = __builtin_amdgcn_readfirstlane(arrived0);
     for (int level = 0;; ++level) {
         const int g = j >> kLogFanIn;
@@ -807,26 +812,37 @@ __device__ __forceinline__ void combine_if_last(const ReduceParams& p, const Cut
     }
 }
 
-// NV: 16-byte fp32 vectors per lane (a wavefront item covers 256 * NV columns); BATCH: sorted
+// NV: 16-byte fp32 vectors per lane (a wavefront covers 256 * NV columns); BATCH: sorted
 // positions whose rows are loaded together.
+//
+// A work-group takes kGroupPieces consecutive pieces of C sorted positions, one per wavefront,
+// and one block of columns.  A wavefront finishes the output rows of at most C pairs that start
+// in its piece; of a longer row it adds up the pairs that lie in its piece and leaves that
+// sum in LDS.  After one barrier the wavefront that holds a row's last piece within the
+// work-group adds the work-group's pieces of that row in piece order; if the row lies inside
+// the work-group it is finished there and then, otherwise the sum goes to scratch as the
+// work-group's share of the row, and the shares are combined as described above.
 template <typename RowT, int NV, int BATCH, int EPI>
 __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
 {
+    // [wavefront][0: of a row that began before the piece, 1: of a row that begins in it][vector][lane]
+    __shared__ f4 chain[kGroupPieces][2][NV][64];
+
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int item = blockIdx.x * 4 + wave;
 
-    if (item >= p.n_piece_items) {
-        // ---- copy item: one output row, copied if it received no pair
-        const int v = p.copy_row0 + item - p.n_piece_items;
+    if ((int)blockIdx.x >= p.n_piece_groups) {
+        // ---- copy: one output row per wavefront, copied if it received no pair
+        const int v = p.copy_row0 + ((int)blockIdx.x - p.n_piece_groups) * kGroupPieces + wave;
         const uint32_t skip = (v < p.copy_row1 && p.count[v] != 0) ? 1u : 0u;
         copy_rows<1, EPI>(p.dense_in, p.dense_out, skip, v, p.copy_row1, p.d, lane, p.scale);
         return;
     }
 
-    // ---- piece item: sorted positions [pos0, pos0 + C), columns [cb*256*NV, (cb+1)*256*NV)
-    const int k = item / p.ncb;
-    const int cb = item - k * p.ncb;
+    // ---- piece k: sorted positions [pos0, pos0 + C), columns [cb*256*NV, (cb+1)*256*NV)
+    const int kg = (int)blockIdx.x / p.ncb;
+    const int cb = (int)blockIdx.x - kg * p.ncb;
+    const int k = kg * kGroupPieces + wave;
     const int col = (cb * kColBlock + lane * 4) * NV;
     const bool colok = col < p.d;
     const int C = p.C;
@@ -845,13 +861,12 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
         r1 = rec[1];
     }
     const int nvalid = *p.n_valid;
-    if (pos0 >= nvalid) return;
     const bool inwin = inarr && wpos < nvalid;
     const int32_t id = inwin ? (int32_t)r0.z : -1;
     const int32_t c = inwin ? (int32_t)r1.x : 0;
     const int32_t s = inwin ? (int32_t)r1.y : 0;
     const uint64_t addr = inwin ? (((uint64_t)r0.y << 32) | r0.x) : 0ull;
-    const bool whole = c <= C;       // output row small enough to be summed by one item
+    const bool whole = c <= C;       // output row small enough to be summed by one wavefront
     const bool active = inwin && (whole ? (s >= pos0 && s < pos0 + C) : (lane < C));
     const bool first = active && (wpos == s || (!whole && lane == 0));
     const bool last = active && (wpos == s + c - 1 || (!whole && lane == C - 1));
@@ -859,96 +874,138 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
     const uint64_t F = ballot64(first);
     const uint64_t Lm = ballot64(last);
     const uint64_t W = ballot64(whole);
-    if (A == 0) return;
-    const int a = __builtin_ctzll(A);
-    const int b = 64 - __builtin_clzll(A);
-    const uint32_t slot = (uint32_t)(2 * k + (s >= pos0 ? 1 : 0));
+    const uint64_t H = ballot64(s >= pos0);      // the row of this position begins in this piece
     const bool have_dense = p.dense_in != nullptr;
 
-    f4 acc[NV];
+    if (A != 0) {
+        const int a = __builtin_ctzll(A);
+        const int b = 64 - __builtin_clzll(A);
+        f4 acc[NV];
 #pragma unroll
-    for (int q = 0; q < NV; ++q) acc[q] = (f4)(0.0f);
-    for (int base = a; base < b; base += BATCH) {
-        f4 r[BATCH][NV], dn[BATCH][NV];
+        for (int q = 0; q < NV; ++q) acc[q] = (f4)(0.0f);
+        for (int base = a; base < b; base += BATCH) {
+            f4 r[BATCH][NV], dn[BATCH][NV];
 #pragma unroll
-        for (int u = 0; u < BATCH; ++u) {
-            const int j = base + u;
+            for (int u = 0; u < BATCH; ++u) {
+                const int j = base + u;
 #pragma unroll
-            for (int q = 0; q < NV; ++q) {
-                r[u][q] = (f4)(0.0f);
-                dn[u][q] = (f4)(0.0f);
-            }
-            if (j < b) {
-                const uint64_t ra = bcast64(addr, j);
-                if (colok) RowLoad<RowT, NV>::load(ra, col, r[u]);
-                if (have_dense && (((Lm & W) >> j) & 1ull)) {
-                    const int vj = (int)bcast((uint32_t)id, j);
-                    if (colok) {
-#pragma unroll
-                        for (int q = 0; q < NV; ++q)
-                            dn[u][q] = load_f4_stream(p.dense_in + (size_t)vj * p.d + col + 4 * q);
-                    }
+                for (int q = 0; q < NV; ++q) {
+                    r[u][q] = (f4)(0.0f);
+                    dn[u][q] = (f4)(0.0f);
                 }
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < BATCH; ++u) {
-            const int j = base + u;
-            if (j < b) {
-                const bool fresh = (F >> j) & 1ull;
-#pragma unroll
-                for (int q = 0; q < NV; ++q) acc[q] = (fresh ? (f4)(0.0f) : acc[q]) + r[u][q];
-                if ((Lm >> j) & 1ull) {
-                    if ((W >> j) & 1ull) {
+                if (j < b) {
+                    const uint64_t ra = bcast64(addr, j);
+                    if (colok) RowLoad<RowT, NV>::load(ra, col, r[u]);
+                    if (have_dense && (((Lm & W) >> j) & 1ull)) {
                         const int vj = (int)bcast((uint32_t)id, j);
                         if (colok) {
 #pragma unroll
                             for (int q = 0; q < NV; ++q)
-                                if constexpr (EPI == EPI_NONE)
-                                    store_f4_stream(reinterpret_cast<float*>(p.dense_out) + (size_t)vj * p.d + col + 4 * q,
-                                                    acc[q] + dn[u][q]);
-                                else
-                                    store_out<EPI>(p.dense_out, (size_t)vj * p.d + col + 4 * q, acc[q] + dn[u][q], p.scale);
+                                dn[u][q] = load_f4_stream(p.dense_in + (size_t)vj * p.d + col + 4 * q);
                         }
-                    } else {
-                        const uint32_t sj = bcast(slot, j);
-                        if (colok) {
+                    }
+                }
+            }
 #pragma unroll
-                            for (int q = 0; q < NV; ++q)
-                                store_f4_through(p.partial + (size_t)sj * p.d + col + 4 * q, acc[q]);
+            for (int u = 0; u < BATCH; ++u) {
+                const int j = base + u;
+                if (j < b) {
+                    const bool fresh = (F >> j) & 1ull;
+#pragma unroll
+                    for (int q = 0; q < NV; ++q) acc[q] = (fresh ? (f4)(0.0f) : acc[q]) + r[u][q];
+                    if ((Lm >> j) & 1ull) {
+                        if ((W >> j) & 1ull) {
+                            const int vj = (int)bcast((uint32_t)id, j);
+                            if (colok) {
+#pragma unroll
+                                for (int q = 0; q < NV; ++q)
+                                    if constexpr (EPI == EPI_NONE)
+                                        store_f4_stream(reinterpret_cast<float*>(p.dense_out) + (size_t)vj * p.d + col + 4 * q,
+                                                        acc[q] + dn[u][q]);
+                                    else
+                                        store_out<EPI>(p.dense_out, (size_t)vj * p.d + col + 4 * q, acc[q] + dn[u][q], p.scale);
+                            }
+                        } else {
+                            const int portion = (int)((H >> j) & 1ull);
+#pragma unroll
+                            for (int q = 0; q < NV; ++q) chain[wave][portion][q][lane] = acc[q];
                         }
                     }
                 }
             }
         }
     }
+    __syncthreads();
 
-    // The shares of cut rows that this item has left in scratch (at most two cut rows pass
-    // through a piece: one that ends in it, one that begins in it) are counted in once their
-    // stores are acknowledged; whoever brings a group's last share adds the group up.
+    // The cut rows that pass through this piece (at most two: one that ends in it or covers
+    // it, one that begins in it).  The wavefront with the row's last piece inside the
+    // work-group adds the work-group's pieces of the row, in piece order.
     uint64_t cuts = Lm & ~W & A;
-    if (cuts == 0) return;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    const int g_first = kg * kGroupPieces, g_last = g_first + kGroupPieces - 1;
     CutRef ref[2];
-    int answer[2];
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        answer[q] = 0;
+    for (int t = 0; t < 2; ++t) {
+        ref[t].k = -1;
         if (cuts) {
             const int j = __builtin_ctzll(cuts);
-            ref[q].k = k;
-            ref[q].id = (int)bcast((uint32_t)id, j);
-            ref[q].s = (int)bcast((uint32_t)s, j);
-            ref[q].c = (int)bcast((uint32_t)c, j);
-            answer[q] = announce_share(p, ref[q], cb, lane);
-        } else {
-            ref[q].k = -1;
-        }
-        cuts &= cuts - 1;
-    }
+            cuts &= cuts - 1;
+            const int idj = (int)bcast((uint32_t)id, j);
+            const int sj = (int)bcast((uint32_t)s, j);
+            const int cj = (int)bcast((uint32_t)c, j);
+            const int piece_first = sj >> p.logC, piece_last = (sj + cj - 1) >> p.logC;
+            if (k == min(piece_last, g_last)) {
+                const bool inside = piece_first >= g_first && piece_last <= g_last;
+                f4 dn[NV];
 #pragma unroll
-    for (int q = 0; q < 2; ++q)
-        if (ref[q].k >= 0) combine_if_last<NV, EPI>(p, ref[q], cb, col, colok, lane, answer[q]);
+                for (int q = 0; q < NV; ++q) {
+                    dn[q] = (f4)(0.0f);
+                    if (inside && have_dense && colok) dn[q] = load_f4_stream(p.dense_in + (size_t)idj * p.d + col + 4 * q);
+                }
+                const int x0 = max(piece_first, g_first);
+                f4 tot[NV];
+#pragma unroll
+                for (int q = 0; q < NV; ++q) tot[q] = chain[x0 - g_first][x0 == piece_first ? 1 : 0][q][lane];
+                for (int x = x0 + 1; x <= k; ++x) {
+#pragma unroll
+                    for (int q = 0; q < NV; ++q) tot[q] += chain[x - g_first][0][q][lane];
+                }
+                if (inside) {
+                    if (colok) {
+#pragma unroll
+                        for (int q = 0; q < NV; ++q) {
+                            if constexpr (EPI == EPI_NONE)
+                                store_f4_stream(reinterpret_cast<float*>(p.dense_out) + (size_t)idj * p.d + col + 4 * q,
+                                                tot[q] + dn[q]);
+                            else
+                                store_out<EPI>(p.dense_out, (size_t)idj * p.d + col + 4 * q, tot[q] + dn[q], p.scale);
+                        }
+                    }
+                } else {
+                    // the work-group's share of a row that goes beyond it
+                    const int kg0 = piece_first >> kLogGroupPieces;
+                    const size_t slot = share_slot(kg0, kg - kg0);
+                    if (colok) {
+#pragma unroll
+                        for (int q = 0; q < NV; ++q) store_f4_through(p.partial + slot * p.d + col + 4 * q, tot[q]);
+                    }
+                    ref[t].k = kg;
+                    ref[t].id = idj;
+                    ref[t].s = sj;
+                    ref[t].c = cj;
+                }
+            }
+        }
+    }
+    if (ref[0].k < 0 && ref[1].k < 0) return;
+    // shares are counted in once their stores are acknowledged; whoever brings the last share
+    // of a group of shares adds the group up
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    int answer[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) answer[t] = ref[t].k >= 0 ? announce_share(p, ref[t], cb, lane) : 0;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+        if (ref[t].k >= 0) combine_if_last<NV, EPI>(p, ref[t], cb, col, colok, lane, answer[t]);
 }
 
 // ------------------------------------------------------------------ unique ids (introspection)
@@ -980,7 +1037,7 @@ __global__ __launch_bounds__(1024) void unique_kernel(const int32_t* count, int 
 
 // ------------------------------------------------------------------ host side
 struct Plan {
-    int32_t S, SL, G, part, list_cap, C, NB, levels, ncb;   // ncb: 256-column blocks of a row; levels of the combine tree
+    int32_t S, SL, G, part, list_cap, C, NB, NBG, levels, ncb;   // NB pieces in NBG groups   // ncb: 256-column blocks of a row; levels of the combine tree
     size_t off_nvalid, off_nbad, off_arrive, arrive_bytes, off_count, off_row_start, off_sorted, off_tot,
         off_below, off_bad, off_partial, total;
 };
@@ -1040,16 +1097,18 @@ void make_plan(int64_t n, int32_t d, int32_t V, int32_t C, Plan* pl)
     pl->G = (V + part - 1) / part;
     pl->C = C;
     pl->NB = (int32_t)((n + pl->C - 1) / pl->C);
-    // a cut row's shares are added up in a tree with a fan-in of 16: levels needed for a row of NB pieces
+    // a work-group of the reduce kernel takes kGroupPieces pieces; the shares of a row that spans several
+    // work-groups are added up in a tree with a fan-in of 16: levels needed for a row that spans them all
+    pl->NBG = (pl->NB + kGroupPieces - 1) / kGroupPieces;
     pl->levels = 1;
-    for (int64_t reach = kFanIn; reach < pl->NB; reach *= kFanIn) ++pl->levels;
+    for (int64_t reach = kFanIn; reach < pl->NBG; reach *= kFanIn) ++pl->levels;
     pl->ncb = (d + kColBlock - 1) / kColBlock;
     size_t o = 0;
     pl->off_nvalid = o;
     pl->off_nbad = o + 4;
     o = 256;
     pl->off_arrive = o;
-    pl->arrive_bytes = align_up((size_t)pl->levels * 2 * pl->NB * pl->ncb * 4, 256);
+    pl->arrive_bytes = align_up((size_t)pl->levels * 2 * pl->NBG * pl->ncb * 4, 256);
     o += pl->arrive_bytes;
     pl->off_count = o;
     o = align_up(o + (size_t)V * 4, 256);
@@ -1064,7 +1123,7 @@ void make_plan(int64_t n, int32_t d, int32_t V, int32_t C, Plan* pl)
     pl->off_bad = o;
     if (pl->S > 1) o = align_up(o + (size_t)pl->S * 4, 256);
     pl->off_partial = o;
-    o = align_up(o + (size_t)2 * pl->NB * (size_t)d * 4, 256);
+    o = align_up(o + (size_t)2 * pl->NBG * (size_t)d * 4, 256);
     pl->total = o;
 }
 
@@ -1211,7 +1270,7 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     rp.d = d;
     rp.C = pl.C;
     rp.ncb = wide ? (d + 2 * kColBlock - 1) / (2 * kColBlock) : pl.ncb;
-    rp.n_piece_items = pl.NB * rp.ncb;
+    rp.n_piece_groups = pl.NBG * rp.ncb;
     rp.count = sp.count;
     rp.sorted = sp.sorted;
     rp.n = (int32_t)n;
@@ -1221,12 +1280,13 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     rp.scale = scale;
     rp.partial = (float*)(ws + pl.off_partial);
     rp.arrive = sp.arrive;
-    rp.nslots = 2 * pl.NB;
+    rp.nslots = 2 * pl.NBG;
     rp.logC = __builtin_ctz((unsigned)pl.C);
+    rp.logG = rp.logC + kLogGroupPieces;
     rp.copy_row0 = copy_done;
     rp.copy_row1 = tail0;
-    const int64_t items = (int64_t)rp.n_piece_items + (skip_untouched ? 0 : tail0 - copy_done);
-    const unsigned rgrid = (unsigned)((items + 3) / 4);
+    const int64_t copy_rows_left = skip_untouched ? 0 : tail0 - copy_done;
+    const unsigned rgrid = (unsigned)(rp.n_piece_groups + (copy_rows_left + kGroupPieces - 1) / kGroupPieces);
 
     const bool prof = g_prof_used < g_prof_cap && rgrid > 0;
     hipEvent_t ev_begin = prof ? g_ev[2 * g_prof_used] : nullptr;

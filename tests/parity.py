@@ -8,8 +8,9 @@ from paper_1905_04035_amd import binding as ts
 from paper_1905_04035_amd import workloads as wl
 
 # fp32 outputs must satisfy |gpu - exact| <= TOL * (sum of |terms| of that element).
-# The library adds at most C <= 32 rows in sequence inside a piece, then the pieces of a
-# cut row in a tree with a fan-in of 16, and dense_in last; with fp32 unit round-off 2^-24
+# The library adds at most C <= 32 rows in sequence inside a piece, the 4 pieces of a
+# work-group in sequence, then the work-groups' shares of a long row in a tree with a fan-in
+# of 16, and dense_in last; with fp32 unit round-off 2^-24
 # the first-order bound is (depth - 1) * 2^-24 * sum|terms|, below 1e-5 for any row of
 # fewer than 16^8 pieces (see error_depth and error_bound below).
 TOL = 1e-5
@@ -95,18 +96,19 @@ def check(g, r: oracle.OracleResult, w: wl.Workload, exact_bits=False):
 
 
 def error_depth(count_max: int, C: int) -> int:
-    """Additions on the longest chain a term of the fullest row can take: C inside a piece; then,
-    per level of the tree in which the shares of a cut row are added up (fan-in 16: one level up
-    to 16 pieces, two up to 256, ...), a balanced tree over a batch of shares followed by the
-    batches in sequence: 4 + 1 for one batch of 16 (fp32 rows), 3 + 2 for two batches of 8 (bf16
-    rows read 16 bytes per lane); dense_in last."""
+    """Additions on the longest chain a term of the fullest row can take: C inside a piece; the
+    4 pieces of a work-group in sequence; then, per level of the tree in which the shares of a
+    row that spans several work-groups are added up (fan-in 16: one level up to 16 work-groups,
+    two up to 256, ...), a balanced tree over a batch of shares followed by the batches in
+    sequence: 4 + 1 for one batch of 16 (fp32 rows), 3 + 2 for two batches of 8 (bf16 rows read
+    16 bytes per lane); dense_in last."""
     if count_max <= C:
         return count_max + 1
-    P = -(-count_max // C) + 1
+    groups = -(-count_max // (4 * C)) + 1
     levels = 1
-    while 16 ** levels < P:
+    while 16 ** levels < groups:
         levels += 1
-    return C + 5 * levels + 1
+    return C + 3 + 5 * levels + 1
 
 
 def error_bound(count_max: int, C: int) -> float:
