@@ -58,6 +58,7 @@ def main():
     ap.add_argument("--overlap-mib", type=float, default=-1.0,
                     help="dense bytes copied beside each sort launch (tuning; -1 = library default)")
     ap.add_argument("--piece-tokens", type=int, default=0, help="tuning; 0 = library default")
+    ap.add_argument("--sort-part", type=int, default=0, help="tuning; 0 = library default")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run the same launches with n = 0: a plain [V, d] copy of known size, used to "
                          "scale hardware byte counters")
@@ -91,6 +92,8 @@ def main():
         ts.ts_set_overlap_bytes(int(args.overlap_mib * (1 << 20)))
     if args.piece_tokens:
         ts.ts_set_piece_tokens(args.piece_tokens)
+    if args.sort_part:
+        ts.ts_set_sort_part(args.sort_part)
 
     if args.tokens > 0:
         args.workload = f"per_worker_batch_{args.tokens}_tokens"
@@ -250,7 +253,7 @@ def main():
     alg_reduce = n * elem * d + (4 + out_elem) * d * (touched + untouched_mid)
     roofline = None
     traffic = None
-    default_tuning = (args.overlap_mib < 0 and not args.piece_tokens and not epilogue)
+    default_tuning = (args.overlap_mib < 0 and not args.piece_tokens and not args.sort_part and not epilogue)
     if default_tuning and args.workload == COUNTED_TRAFFIC["workload"]:
         import hashlib
         src = os.path.join(ROOT, "paper_1905_04035_amd", "csrc", "ts_densify.hip")

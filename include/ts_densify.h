@@ -34,7 +34,10 @@
  *     inputs give the same bits on every run.
  *   - Return value: TS_OK or a ts_status; it covers only what the host can check
  *     (arguments, workspace, launch errors).
- *   - One call at a time per process: calls share the bound workspace.
+ *   - One call at a time per process: calls share the bound workspace, and the library
+ *     remembers which workspace and shapes the most recent call used (for ts_last_views and
+ *     ts_unique_ids).  The calls declared in ts_densify_tools.h (tests, benchmarks, tuning)
+ *     change process-wide settings; none of them is needed to use the library.
  */
 #ifndef TS_DENSIFY_H
 #define TS_DENSIFY_H
@@ -75,9 +78,9 @@ int ts_densify(const int32_t* ids, const float* rows, int64_t n, int32_t d, int3
  * arguments, same kernels, same bits as ts_densify; the workspace is an array built into
  * the library's device image, TS_STATIC_SCRATCH_BYTES per GPU, held by every GPU the
  * library is loaded on until the process ends.  The call allocates and frees nothing and
- * ignores the bound workspace.  It serves the calls whose workspace fits the array, i.e.
- * ts_workspace_bytes-many bytes for fp32 rows <= TS_STATIC_SCRATCH_BYTES (V = 32768,
- * d = 1024: up to about 32 thousand pairs); a larger call returns TS_ERR_CAPACITY before
+ * ignores the bound workspace.  It serves the calls whose own workspace fits the array
+ * (V = 32768, d = 1024: up to about 150 thousand pairs; ts_workspace_bytes(n, d, V) <=
+ * TS_STATIC_SCRATCH_BYTES is sufficient); a larger call returns TS_ERR_CAPACITY before
  * anything is enqueued.  Every call on a GPU uses that GPU's one array: two such calls that
  * overlap in time on one GPU (two streams, two threads) race; calls on one stream do not.
  * Nothing in the array has to survive from call to call, and each call clears what it
@@ -232,62 +235,11 @@ int ts_last_views(const int32_t** count, const int32_t** row_start, const void**
                   const int32_t** n_valid, const int32_t** n_bad_ids);
 
 /*
- * The same, copied to host arrays, for tests and tools: waits for `stream`, then copies
- * count [V] and row_start [V + 1] (int32), the first n_valid sorted records
- * (TS_SORTED_PAIR_BYTES each) and the two scalars.  Any out-pointer may be NULL.  V is that
- * of the most recent call (the number of rows of the range for ts_densify_range), which the
- * library knows and the caller states: count_out holds rows_capacity int32 and row_start_out
- * rows_capacity + 1; TS_ERR_CAPACITY, with nothing written, if the last call's V exceeds
- * rows_capacity, and likewise if n_valid exceeds sorted_capacity records.  This call
- * synchronises.
- */
-int ts_read_views(int32_t* count_out, int32_t* row_start_out, int64_t rows_capacity, void* sorted_out,
-                  int64_t sorted_capacity, int32_t* n_valid_out, int32_t* n_bad_ids_out, void* stream);
-
-/*
- * How the most recent call was split over its launches, for byte accounting in
- * benchmarks.  Writes 8 int32 to info (host): [0] piece_tokens C; [1] X: dense rows
- * [0, X) were copied beside the sort launches; [2] T = V: untouched rows in [X, T) were
- * copied by the row-reduce kernel; [3] sort slices; [4] ids per sort work-group;
- * [5] pieces; [6] levels of the tree in which the shares of a cut row are added up;
- * [7] 1 if the call was in place.
- */
-int ts_last_launch_info(int32_t* info);
-
-/*
  * Ascending list of the rows that received at least one pair in the most recent
  * call: writes unique_ids_out[0 .. n_unique) (device, capacity >= min(n, V)
  * int32) and *n_unique_out (device int32).  Enqueues one small kernel.
  */
 int ts_unique_ids(int32_t* unique_ids_out, int32_t* n_unique_out, void* stream);
-
-/*
- * Per-kernel timing for benchmarks.  ts_profile_begin(capacity) makes each of the
- * next `capacity` densify calls stamp a HIP event pair with the begin and the end of
- * its row-reduce kernel (the launch variant that takes events) on the caller's stream; ts_profile_end waits for those events and writes
- * up to `capacity` durations in milliseconds to ms_out (host) and how many to
- * *n_out (host), then stops recording.  capacity <= 4096.
- */
-int ts_profile_begin(int32_t capacity);
-int ts_profile_end(float* ms_out, int32_t capacity, int32_t* n_out);
-
-/*
- * Tuning.  piece_tokens: sorted positions handled by one wavefront item of the
- * row-reduce kernel (8, 16 or 32; 0 = choose from n and the row type).  Changes the fixed
- * summation order (still deterministic) and the workspace size.
- */
-int ts_set_piece_tokens(int32_t piece_tokens);
-
-/*
- * Tuning.  The sort launches are latency-bound, so work-groups that copy dense rows run
- * beside them to keep HBM busy.  sort_bytes: dense bytes (read + write) copied from dense_in
- * to dense_out beside each sort launch, before it is known which rows receive pairs (those
- * are overwritten afterwards).  -1 = default, 0 = none.  Results do not depend on it.
- */
-int ts_set_overlap_bytes(int64_t sort_bytes);
-
-/* Tuning.  Ids owned by one sort work-group (64 .. 2048, power of two; 0 = choose from V and n). */
-int ts_set_sort_part(int32_t part);
 
 const char* ts_status_string(int status);
 

@@ -1,4 +1,5 @@
-"""ctypes binding of libts_densify.so: the same names as include/ts_densify.h.
+"""ctypes binding of libts_densify.so: the same names as include/ts_densify.h and
+include/ts_densify_tools.h (the calls for tests, benchmarks and tuning).
 
 Argument marshalling only.  Tensors are PyTorch tensors on the GPU (PyTorch is
 used for device memory and streams, nothing else); every step of the path runs
@@ -61,6 +62,7 @@ def lib():
         l.ts_accumulate_strategy.argtypes = [vp, i32, i32, vp]
         l.ts_accumulate.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, i64, vp, vp, vp]
         l.ts_workspace_bytes.argtypes = [i64, i32, i32, vp]
+        l.ts_call_workspace_bytes.argtypes = [i64, i32, i32, i32, vp]
         l.ts_bind_workspace.argtypes = [vp, i64]
         l.ts_last_views.argtypes = [vp, vp, vp, vp, vp]
         l.ts_read_views.argtypes = [vp, vp, i64, vp, i64, vp, vp, vp]
@@ -76,7 +78,7 @@ def lib():
         for name in ("ts_densify", "ts_densify_static", "ts_densify_bf16", "ts_densify_multi", "ts_buffer_bytes",
                      "ts_densify_scaled", "ts_fusion_place", "ts_densify_range",
                      "ts_accumulate_strategy", "ts_accumulate",
-                     "ts_workspace_bytes", "ts_bind_workspace", "ts_last_views", "ts_read_views", "ts_unique_ids",
+                     "ts_workspace_bytes", "ts_call_workspace_bytes", "ts_bind_workspace", "ts_last_views", "ts_read_views", "ts_unique_ids",
                      "ts_last_launch_info",
                      "ts_profile_begin", "ts_profile_end", "ts_set_piece_tokens", "ts_set_overlap_bytes", "ts_set_sort_part"):
             getattr(l, name).restype = C.c_int
@@ -261,6 +263,13 @@ def ts_buffer_bytes(k: int, N: int, d: int, V: int, row_dtype: int = TS_ROW_FP32
 def ts_workspace_bytes(n_total: int, d: int, V: int) -> int:
     b = C.c_int64(0)
     _check(lib().ts_workspace_bytes(n_total, d, V, C.byref(b)), "ts_workspace_bytes")
+    return b.value
+
+
+def ts_call_workspace_bytes(n_total: int, row_dtype: int, d: int, V: int) -> int:
+    """Bytes of workspace a call of exactly this shape uses (host arithmetic)."""
+    b = C.c_int64(0)
+    _check(lib().ts_call_workspace_bytes(n_total, row_dtype, d, V, C.byref(b)), "ts_call_workspace_bytes")
     return b.value
 
 

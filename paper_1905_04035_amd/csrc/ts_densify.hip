@@ -47,6 +47,7 @@
 #include <string.h>
 
 #include "ts_densify.h"
+#include "ts_densify_tools.h"
 
 // Built-in workspace of ts_densify_static, the entry point for callers that cannot allocate.
 // One copy per GPU, held from the moment the library is loaded on it until the process
@@ -1067,7 +1068,10 @@ int piece_tokens_for(int64_t n, bool wide_bf16)
     return (wide_bf16 || n <= kPieceSmallMax) ? 16 : 32;
 }
 
-void make_plan(int64_t n, int32_t d, int32_t V, int32_t C, Plan* pl)
+// bound: size the arrays that depend on how the sort is split (slices, parts) for the largest
+// split any call of at most n pairs and at most V rows can choose, so that the total never
+// shrinks when n or V grows.
+void make_plan(int64_t n, int32_t d, int32_t V, int32_t C, Plan* pl, bool bound = false)
 {
     if (n <= kFusedSortMax) {
         pl->S = 1;
@@ -1116,12 +1120,19 @@ void make_plan(int64_t n, int32_t d, int32_t V, int32_t C, Plan* pl)
     o = align_up(o + ((size_t)V + 1) * 4, 256);
     pl->off_sorted = o;
     o = align_up(o + (size_t)n * sizeof(SortedPair), 256);
+    size_t S_tab = pl->S > 1 ? (size_t)pl->S : 0, ids_tab = (size_t)pl->G * pl->part, G_tab = (size_t)pl->G;
+    if (bound && n > kFusedSortMax) {
+        const size_t s16 = (size_t)((n + kSliceTokens - 1) / kSliceTokens);
+        S_tab = s16 < (size_t)kMaxSlices ? s16 : (size_t)kMaxSlices;
+        ids_tab = align_up((size_t)V, kMaxPart);
+        G_tab = ((size_t)V + 63) / 64;
+    }
     pl->off_tot = o;
-    if (pl->S > 1) o = align_up(o + (size_t)pl->S * pl->G * pl->part * 4, 256);
+    if (S_tab) o = align_up(o + S_tab * ids_tab * 4, 256);
     pl->off_below = o;
-    if (pl->S > 1) o = align_up(o + (size_t)pl->S * pl->G * 4, 256);
+    if (S_tab) o = align_up(o + S_tab * G_tab * 4, 256);
     pl->off_bad = o;
-    if (pl->S > 1) o = align_up(o + (size_t)pl->S * 4, 256);
+    if (S_tab) o = align_up(o + S_tab * 4, 256);
     pl->off_partial = o;
     o = align_up(o + (size_t)2 * pl->NBG * (size_t)d * 4, 256);
     pl->total = o;
@@ -1465,7 +1476,19 @@ int ts_workspace_bytes(int64_t n_total, int32_t d, int32_t V, int64_t* bytes)
     if (n_total >= ((int64_t)1 << 31)) return TS_ERR_OVERFLOW;
     // the smallest pieces a call of this size can use: the most pieces, the largest workspace
     Plan a;
-    make_plan(n_total, d, V, piece_tokens_for(n_total, true), &a);
+    make_plan(n_total, d, V, piece_tokens_for(n_total, true), &a, true);
+    *bytes = (int64_t)a.total;
+    return TS_OK;
+}
+
+int ts_call_workspace_bytes(int64_t n_total, int32_t row_dtype, int32_t d, int32_t V, int64_t* bytes)
+{
+    if (!bytes) return TS_ERR_NULL;
+    if (n_total < 0 || V <= 0 || d <= 0 || (d % 4) != 0) return TS_ERR_SHAPE;
+    if (row_dtype != TS_ROW_FP32 && row_dtype != TS_ROW_BF16) return TS_ERR_SHAPE;
+    if (n_total >= ((int64_t)1 << 31)) return TS_ERR_OVERFLOW;
+    Plan a;
+    make_plan(n_total, d, V, piece_tokens_for(n_total, row_dtype == TS_ROW_BF16 && (d % 8) == 0), &a);
     *bytes = (int64_t)a.total;
     return TS_OK;
 }

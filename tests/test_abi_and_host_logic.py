@@ -10,7 +10,7 @@ from paper_1905_04035_amd import binding as ts
 from paper_1905_04035_amd import build as hip_build
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "ts_densify.h")
+HEADERS = [os.path.join(ROOT, "include", "ts_densify.h"), os.path.join(ROOT, "include", "ts_densify_tools.h")]
 
 
 @pytest.fixture(scope="module")
@@ -19,15 +19,23 @@ def lib():
     return ts.lib()
 
 
-def declared_functions():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(ts_[a-z0-9_]+)\s*\(", text)))
+def declared_functions(headers=HEADERS):
+    names = set()
+    for h in headers:
+        text = open(h).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(ts_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert {"ts_densify", "ts_densify_bf16", "ts_densify_multi", "ts_buffer_bytes"} <= set(names)
+    # the library's own calls and the calls for tests, benchmarks and tuning live in separate headers
+    api, tools = set(declared_functions(HEADERS[:1])), set(declared_functions(HEADERS[1:]))
+    assert {"ts_read_views", "ts_last_launch_info", "ts_profile_begin", "ts_set_piece_tokens"} <= tools
+    assert not (api & tools)
+    assert not any(n.startswith(("ts_set_", "ts_profile_")) for n in api)
     for name in names:
         assert hasattr(lib, name), f"{name} is declared in the header but not exported"
 
@@ -70,6 +78,31 @@ def test_workspace_bytes(lib):
     assert lib.ts_workspace_bytes(-1, 4, 10, C.byref(out)) == ts.TS_ERR_SHAPE
     assert lib.ts_workspace_bytes(2 ** 31, 4, 10, C.byref(out)) == ts.TS_ERR_OVERFLOW
     assert lib.ts_workspace_bytes(10, 4, 10, None) == ts.TS_ERR_NULL
+
+
+@pytest.mark.parametrize("V,d", [(32768, 1024), (32768, 64), (3000, 8), (1 << 20, 64), (1000, 260)])
+def test_workspace_bound_once_serves_every_smaller_call(lib, V, d):
+    # ts_workspace_bytes(n) must never shrink as n grows, and must cover what any call of at most
+    # n pairs uses -- also where the sort changes its split: one slice up to 57344 pairs, slices of
+    # 16384 pairs beyond, longer slices beyond 64 of them (where the slice count can drop again)
+    edges = [0, 1, 1023, 1024, 16384, 16385, 57344, 57345, 65536, 131072, 262144, 1048576, 1048577,
+             1048576 + 16384, 1500000, 2000000, 3000000, 20000000]
+    grid = sorted(set(edges + [e + k for e in edges for k in (-1, 1, 2, 1025) if e + k >= 0]
+                      + list(range(1040000, 1120000, 1777))))
+    prev = 0
+    for n in grid:
+        bound = ts.ts_workspace_bytes(n, d, V)
+        assert bound >= prev, (n, bound, prev)
+        prev = bound
+        for dt in (ts.TS_ROW_FP32, ts.TS_ROW_BF16):
+            assert ts.ts_call_workspace_bytes(n, dt, d, V) <= bound, (n, dt)
+    # a workspace sized for n_total serves every smaller call, smaller V and d included
+    for n_total in (57345, 1048576, 1100000, 20000000):
+        bound = ts.ts_workspace_bytes(n_total, d, V)
+        for n in grid:
+            if n <= n_total:
+                assert ts.ts_call_workspace_bytes(n, ts.TS_ROW_FP32, d, V) <= bound, (n_total, n)
+                assert ts.ts_call_workspace_bytes(n, ts.TS_ROW_BF16, d, max(1, V // 3)) <= bound, (n_total, n)
 
 
 def test_argument_checks_happen_before_any_launch(lib):
