@@ -6,7 +6,7 @@
 //
 //     dense_out[v,:] = dense_in[v,:] + sum_{t : ids[t] == v} rows[t,:]
 //
-// Three launches per call (four when the pairs need more than one sort slice), all on the
+// Two launches per call (three when the pairs need more than one sort slice), all on the
 // caller's stream, no host synchronisation, no allocation:
 //
 //   sort_kernel     stable counting sort of the pairs by id.  Work-group (g, s) owns `part`
@@ -20,23 +20,22 @@
 //                   wait for one another.  With one slice (up to 57344 pairs) this is a
 //                   single launch; with more, a counting launch fills a [slice][id]
 //                   table first.  The sort leaves one 32-byte record per sorted pair.
-//   reduce_kernel   the HBM-bound kernel.  Wavefront items come in two kinds, heavy
-//                   first: (piece of C sorted positions, block of 256 columns), which
-//                   adds the value rows of every output row that starts in the piece
-//                   and writes dense_in + sum straight to dense_out; then (one
-//                   untouched output row), a 16-byte-per-lane streaming copy.  An
-//                   output row with more than C pairs is cut at piece boundaries; its
-//                   pieces go to scratch as fp32 partial rows.
-//   combine_kernel  for every cut row: partials added in piece order by 16 wavefronts
-//                   (contiguous shares, then the shares in order), dense_in added
-//                   last, result written to dense_out.
+//   reduce_kernel   the HBM-bound kernel.  First the work-groups that add value rows: each
+//                   takes four consecutive pieces of C sorted positions (one per wavefront)
+//                   and one block of 256 columns.  A wavefront finishes every output row of
+//                   at most C pairs that starts in its piece (dense_in + sum straight to
+//                   dense_out); the pieces of a longer row are added up through LDS by the
+//                   wavefront that holds the row's last piece in the work-group.  A row
+//                   that spans several work-groups leaves one fp32 share per work-group in
+//                   scratch; arrival counters tell the work-group that brings the last
+//                   share, which adds the shares in a fixed tree order, adds dense_in and
+//                   writes the row.  Then the work-groups that copy untouched output rows,
+//                   16 bytes per lane, streaming.
 //
-// The sort and the combine are chains of memory latencies that move almost nothing, so
-// their launches also carry work-groups that copy dense rows and keep HBM busy: beside a
-// single-slice sort, rows [0, X) are copied before it is known which of them receive
-// pairs (the reduce and combine kernels, which run later, overwrite those); beside the
-// combine, the untouched rows of [T, V).  The reduce kernel copies the untouched rows of
-// [X, T).
+// The sort is a chain of memory latencies that moves almost nothing, so a single-slice sort
+// launch also carries work-groups that copy dense rows [0, X) and keep HBM busy, before it
+// is known which of them receive pairs (the reduce kernel, which runs later, overwrites
+// those).  The reduce kernel copies the untouched rows of [X, V).
 //
 // No floating-point atomics anywhere: the position of every pair, the cut points and
 // the order of every addition depend on the ids alone, so results are reproducible
