@@ -24,14 +24,19 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0
 
-# HBM bytes per reduce_kernel launch on the default workload with default tuning, from the two
-# rocprofv3 --pmc runs summarised in profiles/ (FETCH_SIZE x 1.989 + WRITE_SIZE x 0.996, the
-# factors a plain copy of known size gives).  Only valid for the kernel source it was taken
-# with: when the source's hash differs, `traffic` is reported as null.
+# HBM bytes per reduce_kernel launch with default tuning, per workload, from the two
+# rocprofv3 --pmc runs summarised in profiles/ (FETCH_SIZE x 1.983 + WRITE_SIZE x 0.992, the
+# factors a plain copy of known size gives: profiles/counter_calibration.md).  Only valid for
+# the kernel source it was taken with: when the source's hash differs, `traffic` is reported
+# as null.
 COUNTED_TRAFFIC = {
-    "source_sha256": "bc7a09fe2d343052fb2a4813ed1a496bd16667a2fe1de76a2130a308da858943",
-    "workload": "transformer_big",
-    "reduce_kernel_bytes_per_launch": 263.31e6,
+    "source_sha256": "a4a404d56f4d4b5a38780f0702ba6cd52074452fe22c248a33ace8c222eac751",
+    "reduce_kernel_bytes_per_launch": {
+        "transformer_big": 294.33e6,
+        "transformer_base": 112.99e6,
+        "large_batch_bf16": 572.31e6,
+        "multi_shard_stress": 1391.99e6,
+    },
 }
 
 
@@ -254,11 +259,11 @@ def main():
     roofline = None
     traffic = None
     default_tuning = (args.overlap_mib < 0 and not args.piece_tokens and not args.sort_part and not epilogue)
-    if default_tuning and args.workload == COUNTED_TRAFFIC["workload"]:
+    if default_tuning and args.workload in COUNTED_TRAFFIC["reduce_kernel_bytes_per_launch"]:
         import hashlib
         src = os.path.join(ROOT, "paper_1905_04035_amd", "csrc", "ts_densify.hip")
         if os.path.exists(src) and hashlib.sha256(open(src, "rb").read()).hexdigest() == COUNTED_TRAFFIC["source_sha256"]:
-            traffic = COUNTED_TRAFFIC["reduce_kernel_bytes_per_launch"]
+            traffic = COUNTED_TRAFFIC["reduce_kernel_bytes_per_launch"][args.workload]
     if kernel_ms:
         k_ms = float(np.mean(kernel_ms))
         ach = alg_reduce / (k_ms * 1e-3) / 1e9
@@ -312,9 +317,10 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32" if elem == 4 else "bf16 rows, f32 sums",
+        "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": args.workload, "V": V, "d": d, "n_pairs": n,
+                   "value_rows": "fp32" if elem == 4 else "bf16 (widened exactly, summed in fp32)",
                    "ids": f"zipf(s={w.spec.zipf_s}) over V, random rank->id permutation",
                    "buffer_sets": len(sets), "entry_point": "ts_densify_scaled" if epilogue else
                    ("ts_densify_multi" if multi else ("ts_densify_bf16" if elem == 2 else "ts_densify")),
