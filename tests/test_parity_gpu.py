@@ -252,6 +252,43 @@ def test_runs_are_bit_identical():
     assert np.array_equal(a["out"].view(np.uint32), c["out"].view(np.uint32))
 
 
+def test_back_to_back_calls_on_one_workspace_keep_their_bits():
+    # Long rows are finished inside the reduce launch by whichever work-group brings a row's last
+    # share, which reads the other work-groups' shares from scratch memory that the previous call
+    # used for other data.  Two different inputs alternate on one workspace, back to back without
+    # host synchronisation; every output must have the bits of its first, synchronised run (a share
+    # read stale from a cache, or before it was written, would show here).
+    wa = wl.make("multi_shard_stress")                       # hottest row: 788 shares, three tree levels
+    wb = wl.make_custom(V=32768, d=1024, n_list=[40000, 30000], zipf_s=1.3, seed=49)
+    dev = []
+    for w in (wa, wb):
+        ids, rows = w.concatenated()
+        dev.append((w, to_dev(ids), to_dev(rows), to_dev(w.dense_in)))
+    ws = ts.Workspace(max(wa.n_total, wb.n_total), 1024, 32768, DEV)
+    try:
+        want = []
+        for w, ids_d, rows_d, dn in dev:
+            out = torch.empty_like(dn)
+            ts.ts_densify(ids_d, rows_d, w.d, w.V, dn, out)
+            torch.cuda.synchronize()
+            want.append(out)
+        r = run_oracle(wa)
+        err = np.abs(want[0].cpu().numpy().astype(np.float64) - r.exact)
+        assert np.all(err <= TOL * r.abs_sum)
+        outs = [[torch.empty_like(dev[0][3]) for _ in range(4)] for _ in range(2)]
+        for rep in range(12):
+            for k, (w, ids_d, rows_d, dn) in enumerate(dev):
+                ts.ts_densify(ids_d, rows_d, w.d, w.V, dn, outs[k][rep % 4])
+            if rep % 4 == 3:
+                torch.cuda.synchronize()
+                for k in range(2):
+                    for o in outs[k]:
+                        assert torch.equal(o.view(torch.int32), want[k].view(torch.int32)), (rep, k)
+                        o.fill_(float("nan"))
+    finally:
+        ws.close()
+
+
 def test_a_call_can_be_captured_in_a_hip_graph_and_replayed():
     # the call enqueues kernels only (no allocation, no host synchronisation, no memset), so it
     # can be recorded once and replayed; every replay must give the eager call's bits
