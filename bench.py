@@ -79,7 +79,7 @@ def main():
                     help="do not record per-kernel HIP events inside the timed region")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+        print("bench.py: the library runs on one GPU only (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
 

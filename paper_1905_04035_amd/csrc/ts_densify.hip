@@ -18,8 +18,9 @@
 //                   A part's first position is the number of pairs with a smaller id,
 //                   which the work-group counts itself while it scans, so parts never
 //                   wait for one another.  With one slice (up to 57344 pairs) this is a
-//                   single launch; with more, a counting launch fills a [slice][id]
-//                   table first.  The sort leaves one 32-byte record per sorted pair.
+//                   single launch; with more, a counting launch (count_kernel: one LDS
+//                   table per work-group, no lists) fills a [slice][id] table first.
+//                   The sort leaves one 32-byte record per sorted pair.
 //   reduce_kernel   the HBM-bound kernel.  First the work-groups that add value rows: each
 //                   takes four consecutive pieces of C sorted positions (one per wavefront)
 //                   and one block of 256 columns.  A wavefront finishes every output row of
@@ -336,7 +337,7 @@ struct SortParams {
     float scale;
 };
 
-enum { SORT_FUSED = 0, SORT_COUNT = 1, SORT_SCATTER = 2 };
+enum { SORT_FUSED = 0, SORT_SCATTER = 2 };
 
 // One wavefront walks its sub-slice [a, b) in rounds of kRoundTiles tiles of 64 pairs.
 // All ids of a round are loaded before any is used, so a round costs one memory
@@ -411,6 +412,159 @@ __device__ __forceinline__ void own_pairs(const int32_t (&idr)[kRoundTiles], int
     }
 }
 
+// The counting launch of a sort that takes several slices: work-group (g, s) counts the pairs of
+// slice s per id of part g (p.tot), those with a valid id below the part (p.below) and those
+// with an id outside the vocabulary (p.bad).  One LDS table for the whole work-group: the order
+// of the pairs does not matter here.  It also clears the arrival counters of the reduce kernel,
+// and the work-groups past the counting ones copy dense rows like those of sort_kernel.
+__global__ __launch_bounds__(1024) void count_kernel(SortParams p, ShardTable sh)
+{
+    extern __shared__ __align__(16) uint32_t tab[];     // [part]
+    __shared__ uint32_t red[2 * kSortWaves];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nsort = p.G * p.S;
+    if ((int)blockIdx.x >= nsort) {
+        const int cw = (int)blockIdx.x - nsort;
+        const int v = p.copy_row0 + (cw * kSortWaves + w) * kBigCopyRows;
+        copy_rows<kBigCopyRows, EPI_NONE>(p.copy_in, p.copy_out, 0u, v, p.copy_row1, p.d, lane, p.scale);
+        return;
+    }
+    const int g = (int)blockIdx.x % p.G;
+    const int sl = (int)blockIdx.x / p.G;
+    const int part = p.part;
+    const int lo = g * part;
+    const uint32_t span = (uint32_t)min(part, p.V - lo);
+
+    const int t0 = sl * p.SL;
+    const int t1 = (int)min((int64_t)p.n, (int64_t)t0 + p.SL);
+    const int L = p.SL / kSortWaves;
+    const int a = (int)min((int64_t)t1, (int64_t)t0 + (int64_t)w * L);
+    const int b = (int)min((int64_t)t1, (int64_t)a + L);
+    const int rounds = (b - a + kRoundPairs - 1) / kRoundPairs;
+    int j0 = 0;
+    while (j0 < sh.k - 1 && sh.off[j0 + 1] <= a) ++j0;
+    int j1 = j0;
+    while (j1 < sh.k - 1 && sh.off[j1 + 1] < b) ++j1;
+    const int32_t* const ids0 = sh.ids[j0];
+    const int off0 = sh.off[j0];
+
+    int32_t idr[kRoundTiles];
+    if (rounds > 0) load_round(sh, j0, j1, ids0, off0, a, b, lane, idr);
+    {
+        u4* const z = reinterpret_cast<u4*>(p.arrive);
+        for (int i = (int)blockIdx.x * 1024 + tid; i < p.arrive_vec; i += nsort * 1024) z[i] = (u4)(0u);
+    }
+    for (int i = tid; i < part; i += 1024) tab[i] = 0u;
+    __syncthreads();
+
+    uint32_t below = 0, bad = 0;
+    for (int r = 0; r < rounds; ++r) {
+        const int a0 = a + r * kRoundPairs;
+        if (r > 0) load_round(sh, j0, j1, ids0, off0, a0, b, lane, idr);
+#pragma unroll
+        for (int u = 0; u < kRoundTiles; ++u) {
+            if (a0 + u * 64 < b) {
+                const bool valid = a0 + u * 64 + lane < b;
+                const uint32_t idg = (uint32_t)idr[u];
+                const uint32_t id = idg - (uint32_t)p.id_base;      // row of the call; wraps to a huge number below the range
+                const uint32_t rel = id - (uint32_t)lo;
+                const bool own = valid && rel < span;
+                below += (uint32_t)__popcll(ballot64(valid && id < (uint32_t)lo));
+                bad += (uint32_t)__popcll(ballot64(valid && idg >= (uint32_t)p.V_total));
+                const uint64_t m = ballot64(own);
+                if (m) {
+                    // the pairs of the id that the first owning lane holds are counted by that lane
+                    // alone (a hot id would otherwise be one LDS atomic per pair), the others one by one
+                    const int ll = __builtin_ctzll(m);
+                    const uint32_t rl = bcast(rel, ll);
+                    const uint64_t sm = ballot64(own && rel == rl);
+                    if (lane == ll) atomicAdd(&tab[rl], (uint32_t)__popcll(sm));
+                    if (own && rel != rl) atomicAdd(&tab[rel], 1u);
+                }
+            }
+        }
+    }
+    if (lane == 0) {
+        red[w] = below;
+        red[kSortWaves + w] = bad;
+    }
+    __syncthreads();
+    const size_t GV = (size_t)p.G * part;
+    for (int i = tid; i < part; i += 1024) p.tot[(size_t)sl * GV + lo + i] = tab[i];
+    if (tid == 0) {
+        uint32_t bl = 0, bd = 0;
+#pragma unroll
+        for (int ww = 0; ww < kSortWaves; ++ww) {
+            bl += red[ww];
+            bd += red[kSortWaves + ww];
+        }
+        p.below[sl * p.G + g] = bl;
+        if (g == 0) p.bad[sl] = bd;
+    }
+}
+
+// The scan phase of sort_kernel for one work-group (see there).  E: consecutive ids per thread.
+template <int MODE, int E>
+__device__ __forceinline__ void scan_part(const SortParams& p, uint32_t* cnt, uint32_t* id_total, uint32_t* id_start,
+                                          uint32_t* wsum, uint32_t base, int part, int lo, uint32_t span, int sl,
+                                          int tid, int lane, int w)
+{
+    typedef uint32_t vec __attribute__((ext_vector_type(E)));
+    const int i = tid * E;                  // first of this thread's ids; part is a multiple of E
+    const bool idt = i < part;
+    vec c[kSortWaves];
+    vec total = (vec)(0u), pre = (vec)(0u);
+    if (idt) {
+#pragma unroll
+        for (int ww = 0; ww < kSortWaves; ++ww) {
+            c[ww] = *reinterpret_cast<const vec*>(cnt + ww * part + i);
+            total += c[ww];
+        }
+        if (MODE == SORT_SCATTER) {
+            total = *reinterpret_cast<const vec*>(id_total + i);     // over all slices, fetched at the start of the kernel
+            pre = *reinterpret_cast<const vec*>(id_start + i);
+        }
+    }
+    uint32_t mine = 0;
+#pragma unroll
+    for (int e = 0; e < E; ++e) mine += total[e];
+    const uint32_t incl = wave_inclusive_scan(mine, lane);
+    if (lane == 63) wsum[w] = incl;
+    __syncthreads();
+    uint32_t woff = 0;
+    for (int ww = 0; ww < kSortWaves; ++ww)
+        if (ww < w) woff += wsum[ww];
+    uint32_t rs = base + woff + incl - mine;        // first sorted position of this thread's first id
+    if (idt) {
+        vec start;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            start[e] = rs;
+            if (sl == 0 && (uint32_t)(i + e) < span) {
+                p.count[lo + i + e] = (int32_t)total[e];
+                p.row_start[lo + i + e] = (int32_t)rs;
+                if (lo + i + e == p.V - 1) {
+                    p.row_start[p.V] = (int32_t)(rs + total[e]);
+                    *p.n_valid = (int32_t)(rs + total[e]);
+                }
+            }
+            rs += total[e];
+        }
+        *reinterpret_cast<vec*>(id_total + i) = total;
+        *reinterpret_cast<vec*>(id_start + i) = start;
+        vec o = start + pre;
+#pragma unroll
+        for (int ww = 0; ww < kSortWaves; ++ww) {
+            *reinterpret_cast<vec*>(cnt + ww * part + i) = o;
+            o += c[ww];
+        }
+    }
+    __syncthreads();
+}
+
 template <int MODE, int EPI>
 __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
 {
@@ -457,18 +611,23 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
     int32_t idr[kRoundTiles];
     if (rounds > 0) load_round(sh, j0, j1, ids0, off0, a, b, lane, idr);
 
-    if (MODE != SORT_SCATTER) {
+    if (MODE == SORT_FUSED) {
         // the first launch of a call clears the arrival counters of the reduce kernel
         u4* const z = reinterpret_cast<u4*>(p.arrive);
         for (int i = (int)blockIdx.x * 1024 + tid; i < p.arrive_vec; i += nsort * 1024) z[i] = (u4)(0u);
     }
 
     const size_t GV = (size_t)p.G * part;
+    uint32_t base_fetched = 0, nbad_fetched = 0;
     if (MODE == SORT_SCATTER) {
-        // Every id's count in all slices and in the slices before this one (thread tid speaks
-        // for ids lo + tid, lo + tid + 1024, ...), sixteen loads in flight at a time, fetched
-        // here so that their latency runs beside the ids' and the clearing of the tables.
-        // Kept where the scan below finds them.
+        // Everything the counting launch has left, fetched here so that the latency runs beside
+        // the ids'.  Per slice (lane s2 speaks for slice s2, at most 64 slices): the pairs below
+        // the part and the bad ids.  Per id (thread tid speaks for ids lo + tid, lo + tid + 1024,
+        // ...): its count in all slices and in the slices before this one, sixteen loads in flight
+        // at a time, kept where the scan below finds them.  (Measured: issuing more of these loads
+        // at once, or issuing them before the tables are cleared, lengthens the launch by 2-3 us.)
+        const uint32_t bl = lane < p.S ? p.below[lane * p.G + g] : 0u;
+        const uint32_t bd = lane < p.S ? p.bad[lane] : 0u;
         for (int i = tid; i < part; i += 1024) {
             uint32_t total = 0, pre = 0;
             for (int sb = 0; sb < p.S; sb += 16) {
@@ -485,6 +644,8 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
             id_total[i] = total;
             id_start[i] = pre;
         }
+        base_fetched = wave_sum(bl);
+        nbad_fetched = wave_sum(bd);
     }
     {
         u4* const c4 = reinterpret_cast<u4*>(cnt);
@@ -496,13 +657,23 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
     uint32_t below = 0, bad = 0, nown = 0;
     bool flushed = false;
     auto count_listed = [&](const uint32_t* l, uint32_t cnt_l) {
-        for (uint32_t t = lane; t < cnt_l; t += 64) atomicAdd(&mycnt[l[t] >> kListPosBits], 1u);
+        // the pairs of the id that the first entry holds are counted by one lane (a hot id
+        // would otherwise be one LDS atomic per pair, all on one address), the others one by one
+        for (uint32_t t0 = 0; t0 < cnt_l; t0 += 64) {
+            const bool has = t0 + lane < cnt_l;
+            const uint32_t rel = has ? l[t0 + lane] >> kListPosBits : 0u;
+            const uint32_t rl = bcast(rel, 0);
+            const uint64_t sm = ballot64(has && rel == rl);
+            if (lane == 0) atomicAdd(&mycnt[rl], (uint32_t)__popcll(sm));
+            if (has && rel != rl) atomicAdd(&mycnt[rel], 1u);
+        }
     };
     for (int r = 0; r < rounds; ++r) {
         const int a0 = a + r * kRoundPairs;
         if (r > 0) load_round(sh, j0, j1, ids0, off0, a0, b, lane, idr);
-        own_pairs<true>(idr, a0, b, (uint32_t)(r * kRoundPairs), lane, lo, span, (uint32_t)p.id_base,
-                        (uint32_t)p.V_total, list, (uint32_t)p.list_cap, nown, below, bad, flushed, count_listed);
+        own_pairs<MODE == SORT_FUSED>(idr, a0, b, (uint32_t)(r * kRoundPairs), lane, lo, span, (uint32_t)p.id_base,
+                                      (uint32_t)p.V_total, list, (uint32_t)p.list_cap, nown, below, bad, flushed,
+                                      count_listed);
     }
     count_listed(list, nown);
     if (lane == 0) {
@@ -518,76 +689,22 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
     }
 
     uint32_t base = below_wg, nbad = bad_wg;       // first sorted position of the part; bad ids
-    if (MODE == SORT_COUNT) {
-        if (tid == 0) {
-            p.below[sl * p.G + g] = below_wg;
-            if (g == 0) p.bad[sl] = bad_wg;
-        }
-    }
     if (MODE == SORT_SCATTER) {
-        // lane s2 fetches slice s2's figures (at most 64 slices): one memory latency for all
-        const uint32_t bl = lane < p.S ? p.below[lane * p.G + g] : 0u;
-        const uint32_t bd = lane < p.S ? p.bad[lane] : 0u;
-        base = wave_sum(bl);
-        nbad = wave_sum(bd);
+        base = base_fetched;
+        nbad = nbad_fetched;
     }
-    if (MODE != SORT_COUNT && sl == 0 && g == 0 && tid == 0) *p.n_bad = (int32_t)nbad;
+    if (sl == 0 && g == 0 && tid == 0) *p.n_bad = (int32_t)nbad;
 
-    // The ids of the part, 1024 at a time (thread tid speaks for id lo + i): totals over the
-    // wavefronts (and slices), exclusive scan into first positions, running positions per
-    // wavefront; each id's count and first position are kept where the ranking pass reads them.
-    uint32_t carry = base;
-    for (int i0 = 0; i0 < part; i0 += 1024) {
-        const int i = i0 + tid;
-        const bool idt = i < part;
-        uint32_t mine = 0;
-        if (idt) {
-#pragma unroll
-            for (int ww = 0; ww < kSortWaves; ++ww) mine += cnt[ww * part + i];
-        }
-        if (MODE == SORT_COUNT) {
-            if (idt) p.tot[(size_t)sl * GV + lo + i] = mine;
-            continue;
-        }
-        uint32_t total = mine, pre = 0;
-        if (MODE == SORT_SCATTER && idt) {
-            total = id_total[i];        // fetched at the start of the kernel, by this thread
-            pre = id_start[i];
-        }
-        const uint32_t incl = wave_inclusive_scan(total, lane);
-        if (lane == 63) red[2 * kSortWaves + w] = incl;
-        __syncthreads();
-        uint32_t woff = 0, block_total = 0;
-        for (int ww = 0; ww < kSortWaves; ++ww) {
-            const uint32_t x = red[2 * kSortWaves + ww];
-            if (ww < w) woff += x;
-            block_total += x;
-        }
-        const uint32_t rs = carry + woff + incl - total;
-        carry += block_total;
-
-        if (sl == 0 && (uint32_t)i < span) {
-            p.count[lo + i] = (int32_t)total;
-            p.row_start[lo + i] = (int32_t)rs;
-            if (lo + i == p.V - 1) {
-                p.row_start[p.V] = (int32_t)(rs + total);
-                *p.n_valid = (int32_t)(rs + total);
-            }
-        }
-        if (idt) {
-            id_total[i] = total;
-            id_start[i] = rs;
-            uint32_t o = rs + pre;
-#pragma unroll
-            for (int ww = 0; ww < kSortWaves; ++ww) {
-                const uint32_t c = cnt[ww * part + i];
-                cnt[ww * part + i] = o;
-                o += c;
-            }
-        }
-        __syncthreads();
+    // The ids of the part in one sweep: thread tid speaks for E = part / 1024 (at least 1)
+    // consecutive ids lo + E*tid .., read and written with one LDS access per table (8 bytes
+    // when E = 2).  Totals over the wavefronts (and slices), exclusive scan into first
+    // positions, running positions per wavefront; each id's count and first position are kept
+    // where the ranking pass reads them.
+    if (part > 1024) {
+        scan_part<MODE, 2>(p, cnt, id_total, id_start, red + 2 * kSortWaves, base, part, lo, span, sl, tid, lane, w);
+    } else {
+        scan_part<MODE, 1>(p, cnt, id_total, id_start, red + 2 * kSortWaves, base, part, lo, span, sl, tid, lane, w);
     }
-    if (MODE == SORT_COUNT) return;
 
     // pass 2: every owned pair takes the next position of its id.  The list keeps the pairs in
     // input order and wavefronts own consecutive sub-slices, so the sort is stable.  Per 64
@@ -1269,7 +1386,7 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
         TS_DISPATCH_EPI(epi, launch_sort_fused, g1, lds, stream, sp, sh);
     } else {
         const dim3 g1 = sort_grid(sp);
-        hipLaunchKernelGGL((sort_kernel<SORT_COUNT, EPI_NONE>), g1, dim3(1024), lds, stream, sp, sh);
+        hipLaunchKernelGGL(count_kernel, g1, dim3(1024), (size_t)pl.part * sizeof(uint32_t), stream, sp, sh);
         const dim3 g2 = sort_grid(sp);
         hipLaunchKernelGGL((sort_kernel<SORT_SCATTER, EPI_NONE>), g2, dim3(1024), lds, stream, sp, sh);
     }
