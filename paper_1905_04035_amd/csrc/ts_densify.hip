@@ -175,32 +175,25 @@ __device__ __forceinline__ void store_f4_through(float* p, f4 v)
     asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
 }
 
-// The matching load: at agent scope, so it is answered from memory and not from a line that
-// this L2 slice or this compute unit's cache may still hold from an earlier call.  The
-// compiler does not see the load: whoever issues a batch of them waits for the batch with
-// loads_done, which also ties the loaded values to the wait.
-__device__ __forceinline__ f4 load_f4_through(const float* p)
+// The matching loads: at agent scope, so they are answered from memory and not from a line
+// that this L2 slice or this compute unit's cache may still hold from an earlier call.  Eight
+// 16-byte loads and the wait for them in ONE statement, so that the compiler never sees a
+// loaded register before its data is there.  All eight addresses must be readable.
+__device__ __forceinline__ void load8_through(f4 (&x)[8], const float* const (&addr)[8])
 {
-    f4 v;
-    asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(p) : "memory");
-    return v;
-}
-
-template <int N>
-__device__ __forceinline__ void loads_done(f4 (&x)[N])
-{
-    static_assert(N == 8 || N == 16, "batch sizes of the combine");
-    if constexpr (N == 16)
-        asm volatile("s_waitcnt vmcnt(0)"
-                     : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7]),
-                       "+v"(x[8]), "+v"(x[9]), "+v"(x[10]), "+v"(x[11]), "+v"(x[12]), "+v"(x[13]), "+v"(x[14]), "+v"(x[15])
-                     :
-                     : "memory");
-    else
-        asm volatile("s_waitcnt vmcnt(0)"
-                     : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7])
-                     :
-                     : "memory");
+    asm volatile(
+        "global_load_dwordx4 %0, %8, off sc1\n\t"
+        "global_load_dwordx4 %1, %9, off sc1\n\t"
+        "global_load_dwordx4 %2, %10, off sc1\n\t"
+        "global_load_dwordx4 %3, %11, off sc1\n\t"
+        "global_load_dwordx4 %4, %12, off sc1\n\t"
+        "global_load_dwordx4 %5, %13, off sc1\n\t"
+        "global_load_dwordx4 %6, %14, off sc1\n\t"
+        "global_load_dwordx4 %7, %15, off sc1\n\t"
+        "s_waitcnt vmcnt(0)"
+        : "=&v"(x[0]), "=&v"(x[1]), "=&v"(x[2]), "=&v"(x[3]), "=&v"(x[4]), "=&v"(x[5]), "=&v"(x[6]), "=&v"(x[7])
+        : "v"(addr[0]), "v"(addr[1]), "v"(addr[2]), "v"(addr[3]), "v"(addr[4]), "v"(addr[5]), "v"(addr[6]), "v"(addr[7])
+        : "memory");
 }
 
 // Streaming accesses for data that is touched once per call (value rows, dense_in,
@@ -814,7 +807,7 @@ constexpr int kLogGroupPieces = 2;
 // rest of the kernel) and without an acquire fence (which empties this L2 slice for
 // everybody): shares are stored through to memory (store_f4_through); a wavefront counts
 // itself in only after those stores have been acknowledged; the wavefront that sees the
-// full count reads the shares from memory (load_f4_through), past its caches.
+// full count reads the shares from memory (load8_through), past its caches.
 constexpr int kFanIn = 16;
 constexpr int kLogFanIn = 4;
 
@@ -854,7 +847,7 @@ template <int NV, int EPI>
 __device__ __forceinline__ void combine_if_last(const ReduceParams& p, const CutRef& r, int cb, int col, bool colok,
                                                 int lane, int arrived0)
 {
-    constexpr int kBatch = 16 / NV;                 // shares loaded together
+    constexpr int kBatch = 8 / NV;                  // shares loaded together: eight 16-byte loads
     const int k0 = r.s >> p.logG;                                     // the row's first group of pieces
     int Pl = ((r.s + r.c - 1) >> p.logG) - k0 + 1;                    // shares at this level (groups at level 0)
     int j = r.k - k0;                                                 // this wavefront's share
@@ -884,19 +877,20 @@ __device__ __forceinline__ void combine_if_last(const ReduceParams& p, const Cut
         f4 tot[NV];
 #pragma unroll
         for (int q = 0; q < NV; ++q) tot[q] = (f4)(0.0f);
+        // lanes past the row's last column read column 0 and drop it; shares past the group's
+        // last read the last one again and drop it: every load is to an address that exists
+        const int safe_col = colok ? col : 0;
         for (int i0 = 0; i0 < m; i0 += kBatch) {
-            f4 x[kBatch * NV];          // share u of the batch, vector q: x[u * NV + q]
+            f4 x[8];                    // share u of the batch, vector q: x[u * NV + q]
+            const float* addr[8];
 #pragma unroll
-            for (int u = 0; u < kBatch; ++u) {
-                const int i = i0 + u;
-                const size_t sl = share_slot(k0, ((g << kLogFanIn) + min(i, m - 1)) << shift);
-#pragma unroll
-                for (int q = 0; q < NV; ++q) {
-                    x[u * NV + q] = (f4)(0.0f);
-                    if (i < m && colok) x[u * NV + q] = load_f4_through(p.partial + sl * p.d + col + 4 * q);
-                }
+            for (int t = 0; t < 8; ++t) {
+                const int i = min(i0 + t / NV, m - 1);
+                addr[t] = p.partial + share_slot(k0, ((g << kLogFanIn) + i) << shift) * p.d + safe_col + 4 * (t % NV);
             }
-            loads_done(x);
+            load8_through(x, addr);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) x[t] = (i0 + t / NV < m && colok) ? x[t] : (f4)(0.0f);
 #pragma unroll
             for (int w = 1; w < kBatch; w <<= 1)
 #pragma unroll

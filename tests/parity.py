@@ -100,7 +100,7 @@ def error_depth(count_max: int, C: int) -> int:
     4 pieces of a work-group in sequence; then, per level of the tree in which the shares of a
     row that spans several work-groups are added up (fan-in 16: one level up to 16 work-groups,
     two up to 256, ...), a balanced tree over a batch of shares followed by the batches in
-    sequence: 4 + 1 for one batch of 16 (fp32 rows), 3 + 2 for two batches of 8 (bf16 rows read
+    sequence: 3 + 2 for two batches of 8 (fp32 rows), 2 + 4 for four batches of 4 (bf16 rows read
     16 bytes per lane); dense_in last."""
     if count_max <= C:
         return count_max + 1
@@ -108,7 +108,7 @@ def error_depth(count_max: int, C: int) -> int:
     levels = 1
     while 16 ** levels < groups:
         levels += 1
-    return C + 3 + 5 * levels + 1
+    return C + 3 + 6 * levels + 1
 
 
 def error_bound(count_max: int, C: int) -> float:
