@@ -170,6 +170,55 @@ def test_piece_sizes_and_exact_boundaries(piece):
         ts.ts_set_piece_tokens(0)
 
 
+@pytest.mark.parametrize("shift", [0, 1, 37])
+@pytest.mark.parametrize("piece", [16, 32])
+def test_rows_at_the_boundaries_of_work_groups_and_of_the_combine_tree(piece, shift):
+    # A reduce work-group takes 4 pieces; a row inside one work-group is finished there, a longer
+    # one leaves a share per work-group, and shares are added up 16 at a time, level by level.
+    # Rows of exactly those sizes, one pair less and one more, starting `shift` sorted positions
+    # after a work-group boundary; small-integer values, so every bit must match.
+    ts.ts_set_piece_tokens(piece)
+    try:
+        G = 4 * piece                       # sorted positions of one work-group
+        counts = [shift] if shift else []
+        for c in (G - 1, G, G + 1, 2 * G, 16 * G - 1, 16 * G, 16 * G + 1, 17 * G, 2, piece + 1, 256 * G + 3, 5):
+            counts.append(c)
+        V, d = 3 * len(counts) + 8, 260      # one full column block and a ragged one
+        ids = np.concatenate([np.full(c, 2 + 3 * i, dtype=np.int32) for i, c in enumerate(counts)])
+        rng = np.random.default_rng(100 * piece + shift)
+        ids = ids[rng.permutation(len(ids))]
+        rows = rng.integers(-4, 5, size=(len(ids), d)).astype(np.float32)
+        dense = rng.integers(-4, 5, size=(V, d)).astype(np.float32)
+        w = wl.Workload(spec=wl.Spec("custom", -1, V, d, 1, 0, "zipf"), ids=[ids], rows=[rows], dense_in=dense)
+        worst, g, r = _case(w, exact_bits=True)
+        assert g["info"]["combine_levels"] >= 3 and int(r.count.max()) == 256 * G + 3
+    finally:
+        ts.ts_set_piece_tokens(0)
+
+
+def test_a_workspace_of_exactly_the_bytes_a_call_uses_is_enough_and_one_byte_less_is_not():
+    w = wl.make_custom(V=5000, d=256, n_list=[70000, 30000], zipf_s=1.3, seed=71)     # a multi-slice call
+    ids, rows = w.concatenated()
+    ids_d, rows_d, dn = to_dev(ids), to_dev(rows), to_dev(w.dense_in)
+    need = ts.ts_call_workspace_bytes(w.n_total, ts.TS_ROW_FP32, w.d, w.V)
+    assert need <= ts.ts_workspace_bytes(w.n_total, w.d, w.V)
+    buf = torch.empty(need, dtype=torch.uint8, device=DEV)
+    out = torch.empty_like(dn)
+    try:
+        assert ts.lib().ts_bind_workspace(buf.data_ptr(), need - 1) == ts.TS_OK
+        with pytest.raises(ts.TsError) as e:
+            ts.ts_densify(ids_d, rows_d, w.d, w.V, dn, out)
+        assert e.value.status == ts.TS_ERR_WORKSPACE
+        assert ts.lib().ts_bind_workspace(buf.data_ptr(), need) == ts.TS_OK
+        ts.ts_densify(ids_d, rows_d, w.d, w.V, dn, out)
+        torch.cuda.synchronize()
+        r = run_oracle(w)
+        err = np.abs(out.cpu().numpy().astype(np.float64) - r.exact)
+        assert np.all(err <= TOL * r.abs_sum)
+    finally:
+        ts.ts_bind_workspace(None)
+
+
 @pytest.mark.parametrize("part", [64, 512, 2048])
 @pytest.mark.parametrize("ids", ["single", "zipf", "uniform"])
 def test_sort_part_sizes_and_lists_of_owned_pairs(part, ids):
