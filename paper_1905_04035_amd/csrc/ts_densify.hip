@@ -262,18 +262,36 @@ __device__ __forceinline__ void copy_rows(const float* dense_in, void* dense_out
                 x[r][u] = (f4)(0.0f);
                 if (go[r] && dense_in && col < d) x[r][u] = load_f4_stream(dense_in + (size_t)(v0 + r) * d + col);
             }
+        // With an epilogue every value is transformed before the first store is issued: a
+        // multiply placed between two stores makes the compiler wait for the earlier store
+        // (the empty asm statements keep it from moving the arithmetic down to the stores).
+        u2 packed[R][4];
+        if constexpr (EPI != EPI_NONE) {
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    x[r][u] = x[r][u] * scale;
+                    if constexpr (EPI == EPI_SCALE_BF16) {
+                        packed[r][u].x = bf16_rne(x[r][u].x) | (bf16_rne(x[r][u].y) << 16);
+                        packed[r][u].y = bf16_rne(x[r][u].z) | (bf16_rne(x[r][u].w) << 16);
+                        asm volatile("" : "+v"(packed[r][u]));
+                    } else {
+                        asm volatile("" : "+v"(x[r][u]));
+                    }
+                }
+        }
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int col = c0 + u * kColBlock + lane * 4;
                 if (go[r] && col < d) {
-                    // (the plain path spelled out: routing it through store_out changes the code
-                    // the compiler makes for it, and that code measured slower)
-                    if constexpr (EPI == EPI_NONE)
-                        store_f4_stream(reinterpret_cast<float*>(dense_out) + (size_t)(v0 + r) * d + col, x[r][u]);
+                    const size_t idx = (size_t)(v0 + r) * d + col;
+                    if constexpr (EPI == EPI_SCALE_BF16)
+                        __builtin_nontemporal_store(packed[r][u], reinterpret_cast<u2*>(reinterpret_cast<uint16_t*>(dense_out) + idx));
                     else
-                        store_out<EPI>(dense_out, (size_t)(v0 + r) * d + col, x[r][u], scale);
+                        store_f4_stream(reinterpret_cast<float*>(dense_out) + idx, x[r][u]);
                 }
             }
     }
@@ -781,12 +799,13 @@ struct ReduceParams {
     const int32_t* n_valid;
     const float* dense_in;
     void* dense_out;
-    float scale;
     float* partial;             // [2 * groups][d]: slot 2g holds group g's share of a row that began before it,
                                 // slot 2g + 1 its share of a row that begins in it and goes on beyond it
     int32_t logC, logG;         // log2 C; log2 of the sorted positions of a group of pieces
     int32_t* arrive;            // [levels][2 * groups][ncb] arrival counters, all zero when the launch starts
     int32_t nslots;             // 2 * groups
+    float scale;                // last: placed between the pointers, the compiler kept a 16-byte slice of the
+                                // argument in LDS, written by every wavefront at its start (+14 % kernel time)
 };
 
 constexpr int kGroupPieces = 4;     // pieces per work-group of the reduce kernel, one per wavefront
