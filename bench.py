@@ -64,6 +64,7 @@ def main():
                     help="dense bytes copied beside each sort launch (tuning; -1 = library default)")
     ap.add_argument("--piece-tokens", type=int, default=0, help="tuning; 0 = library default")
     ap.add_argument("--sort-part", type=int, default=0, help="tuning; 0 = library default")
+    ap.add_argument("--short-rows", type=int, default=-1, help="tuning; -1 = library default, 0 = in the pieces, 1 = row by row")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run the same launches with n = 0: a plain [V, d] copy of known size, used to "
                          "scale hardware byte counters")
@@ -99,6 +100,8 @@ def main():
         ts.ts_set_piece_tokens(args.piece_tokens)
     if args.sort_part:
         ts.ts_set_sort_part(args.sort_part)
+    if args.short_rows >= 0:
+        ts.ts_set_short_rows(args.short_rows)
 
     if args.tokens > 0:
         args.workload = f"per_worker_batch_{args.tokens}_tokens"
@@ -258,7 +261,7 @@ def main():
     alg_reduce = n * elem * d + (4 + out_elem) * d * (touched + untouched_mid)
     roofline = None
     traffic = None
-    default_tuning = (args.overlap_mib < 0 and not args.piece_tokens and not args.sort_part and not epilogue)
+    default_tuning = (args.overlap_mib < 0 and not args.piece_tokens and not args.sort_part and args.short_rows < 0 and not epilogue)
     if default_tuning and args.workload in COUNTED_TRAFFIC["reduce_kernel_bytes_per_launch"]:
         import hashlib
         src = os.path.join(ROOT, "paper_1905_04035_amd", "csrc", "ts_densify.hip")

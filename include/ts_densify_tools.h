@@ -72,6 +72,13 @@ int ts_set_piece_tokens(int32_t piece_tokens);
  */
 int ts_set_overlap_bytes(int64_t sort_bytes);
 
+/*
+ * Tuning.  Output rows with at most piece_tokens pairs are added up either by the pieces
+ * that hold their pairs (mode 0) or row by row, by the wavefront that would otherwise copy
+ * the row (mode 1).  -1 = choose from the number of pairs.  Results do not depend on it.
+ */
+int ts_set_short_rows(int32_t mode);
+
 /* Tuning.  Ids owned by one sort work-group (64 .. 2048, power of two; 0 = choose from V and n). */
 int ts_set_sort_part(int32_t part);
 

@@ -73,6 +73,7 @@ def lib():
         l.ts_set_piece_tokens.argtypes = [i32]
         l.ts_set_overlap_bytes.argtypes = [i64]
         l.ts_set_sort_part.argtypes = [i32]
+        l.ts_set_short_rows.argtypes = [i32]
         l.ts_status_string.argtypes = [C.c_int]
         l.ts_status_string.restype = C.c_char_p
         for name in ("ts_densify", "ts_densify_static", "ts_densify_bf16", "ts_densify_multi", "ts_buffer_bytes",
@@ -80,7 +81,7 @@ def lib():
                      "ts_accumulate_strategy", "ts_accumulate",
                      "ts_workspace_bytes", "ts_call_workspace_bytes", "ts_bind_workspace", "ts_last_views", "ts_read_views", "ts_unique_ids",
                      "ts_last_launch_info",
-                     "ts_profile_begin", "ts_profile_end", "ts_set_piece_tokens", "ts_set_overlap_bytes", "ts_set_sort_part"):
+                     "ts_profile_begin", "ts_profile_end", "ts_set_piece_tokens", "ts_set_overlap_bytes", "ts_set_sort_part", "ts_set_short_rows"):
             getattr(l, name).restype = C.c_int
         _lib = l
     return _lib
@@ -356,5 +357,5 @@ def ts_set_sort_part(part: int) -> None:
     _check(lib().ts_set_sort_part(part), "ts_set_sort_part")
 
 
-def ts_set_combine_groups(groups: int) -> None:
-    _check(lib().ts_set_combine_groups(groups), "ts_set_combine_groups")
+def ts_set_short_rows(mode: int) -> None:
+    _check(lib().ts_set_short_rows(mode), "ts_set_short_rows")

@@ -80,6 +80,7 @@ constexpr int kSortWaves = 16;     // wavefronts per sort work-group
 constexpr int kColBlock = 256;     // fp32 columns per wavefront item (64 lanes x 4)
 constexpr int kMaxSlices = 64;
 constexpr int kSliceTokens = 16384;
+constexpr int64_t kShortRowsFrom = 49152;   // calls with at least this many pairs add up their short rows row by row
 constexpr int kFusedSortMax = 57344;   // up to here one launch sorts everything (measured against two launches)
 constexpr int kPieceSmallMax = 16384;  // up to here pieces of 16 positions, above 32 (bf16 rows read 16 bytes
                                        // per lane: always 16) -- measured
@@ -101,6 +102,10 @@ __device__ __forceinline__ uint64_t bcast64(uint64_t x, int lane)
     return ((uint64_t)hi << 32) | lo;
 }
 
+// Waits until every vector memory operation of the wavefront has completed (vmcnt = 0, the
+// other counters left alone).  The builtin, not an asm statement: the compiler takes note of it.
+__device__ __forceinline__ void wait_vm_all() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 __device__ __forceinline__ uint32_t wave_sum(uint32_t x)
 {
 #pragma unroll
@@ -118,18 +123,22 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x, int lane)
     return x;
 }
 
-// Value rows: 4 * NV consecutive columns per lane, widened to fp32.  (The address arrives as
-// an integer: say that it is global memory, or the compiler falls back to flat loads.)
+// Value rows: 4 * NV consecutive columns per lane.  load() brings them as they lie in memory
+// (Raw: what stays in registers while the load is in flight), widen() makes fp32 of them.  (The
+// address arrives as an integer: say that it is global memory, or the compiler falls back to
+// flat loads.)
 template <typename RowT, int NV>
 struct RowLoad;
 
 template <>
 struct RowLoad<float, 1> {
-    static __device__ __forceinline__ void load(uint64_t row_addr, int col, f4 (&out)[1])
+    typedef f4 Raw;
+    static __device__ __forceinline__ Raw load(uint64_t row_addr, int col)
     {
         typedef const f4 __attribute__((address_space(1))) * global_f4;
-        out[0] = __builtin_nontemporal_load(reinterpret_cast<global_f4>(row_addr + (uint64_t)col * 4u));
+        return __builtin_nontemporal_load(reinterpret_cast<global_f4>(row_addr + (uint64_t)col * 4u));
     }
+    static __device__ __forceinline__ void widen(Raw b, f4 (&out)[1]) { out[0] = b; }
 };
 
 __device__ __forceinline__ f4 widen_bf16x4(uint32_t lo, uint32_t hi)
@@ -144,21 +153,26 @@ __device__ __forceinline__ f4 widen_bf16x4(uint32_t lo, uint32_t hi)
 
 template <>
 struct RowLoad<uint16_t, 1> {
-    static __device__ __forceinline__ void load(uint64_t row_addr, int col, f4 (&out)[1])
+    typedef u2 Raw;
+    static __device__ __forceinline__ Raw load(uint64_t row_addr, int col)
     {
         typedef const u2 __attribute__((address_space(1))) * global_u2;
-        const u2 b = __builtin_nontemporal_load(reinterpret_cast<global_u2>(row_addr + (uint64_t)col * 2u));
-        out[0] = widen_bf16x4(b.x, b.y);
+        return __builtin_nontemporal_load(reinterpret_cast<global_u2>(row_addr + (uint64_t)col * 2u));
     }
+    static __device__ __forceinline__ void widen(Raw b, f4 (&out)[1]) { out[0] = widen_bf16x4(b.x, b.y); }
 };
 
 // bf16 rows with d % 8 == 0: one 16-byte load brings eight columns
 template <>
 struct RowLoad<uint16_t, 2> {
-    static __device__ __forceinline__ void load(uint64_t row_addr, int col, f4 (&out)[2])
+    typedef u4 Raw;
+    static __device__ __forceinline__ Raw load(uint64_t row_addr, int col)
     {
         typedef const u4 __attribute__((address_space(1))) * global_u4;
-        const u4 b = __builtin_nontemporal_load(reinterpret_cast<global_u4>(row_addr + (uint64_t)col * 2u));
+        return __builtin_nontemporal_load(reinterpret_cast<global_u4>(row_addr + (uint64_t)col * 2u));
+    }
+    static __device__ __forceinline__ void widen(Raw b, f4 (&out)[2])
+    {
         out[0] = widen_bf16x4(b.x, b.y);
         out[1] = widen_bf16x4(b.z, b.w);
     }
@@ -790,22 +804,27 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
 
 // ------------------------------------------------------------------ reduce
 struct ReduceParams {
+    // the first 64 bytes: all that a wavefront which copies a row needs
     int32_t V, d, C, ncb;
     int32_t n_piece_groups;     // work-groups that sum pieces: (groups of kGroupPieces pieces) x column blocks
-    int32_t copy_row0, copy_row1;   // the work-groups after them copy the untouched rows in this range
+    int32_t row0;               // the work-groups after them take the rows from here on, one per wavefront
+    int32_t short_max;          // rows with at most this many pairs are added up row by row (0 or C)
+    int32_t copy_row0;          // untouched rows below this one have been copied by the sort launches
     const int32_t* count;
-    const SortedPair* sorted;
-    int32_t n;                  // pairs in the call (records beyond n_valid hold nothing)
-    const int32_t* n_valid;
     const float* dense_in;
     void* dense_out;
+    float scale;
+    int32_t copy_untouched;     // 0: rows without pairs are left as they are (in place, no epilogue)
+    // the rest
+    const int32_t* row_start;
+    const SortedPair* sorted;
+    const int32_t* n_valid;
+    int32_t n;                  // pairs in the call (records beyond n_valid hold nothing)
+    int32_t nslots;             // 2 * groups
     float* partial;             // [2 * groups][d]: slot 2g holds group g's share of a row that began before it,
                                 // slot 2g + 1 its share of a row that begins in it and goes on beyond it
-    int32_t logC, logG;         // log2 C; log2 of the sorted positions of a group of pieces
     int32_t* arrive;            // [levels][2 * groups][ncb] arrival counters, all zero when the launch starts
-    int32_t nslots;             // 2 * groups
-    float scale;                // last: placed between the pointers, the compiler kept a 16-byte slice of the
-                                // argument in LDS, written by every wavefront at its start (+14 % kernel time)
+    int32_t logC, logG;         // log2 C; log2 of the sorted positions of a group of pieces
 };
 
 constexpr int kGroupPieces = 4;     // pieces per work-group of the reduce kernel, one per wavefront
@@ -942,17 +961,91 @@ __device__ __forceinline__ void combine_if_last(const ReduceParams& p, const Cut
     }
 }
 
-// NV: 16-byte fp32 vectors per lane (a wavefront covers 256 * NV columns); BATCH: sorted
-// positions whose rows are loaded together.
+// One output row v (all its columns), by one wavefront, when rows with at most short_max (> 0)
+// pairs are added up row by row.  A row that received no pair is copied from dense_in, unless
+// that has been done or is not wanted; of a row that received at most short_max pairs, the
+// value rows are added up in sorted order and dense_in last.  (Longer rows belong to the
+// pieces.)  dense_in is asked for before the row's count is known whenever it will most
+// likely be needed: all but the few long rows need it then.
+template <typename RowT, int EPI>
+__device__ __forceinline__ void short_row(const ReduceParams& p, int v, int lane)
+{
+    const bool copy = p.copy_untouched && v >= p.copy_row0;
+    const bool early = copy;
+    constexpr int RB = sizeof(RowT) == 4 ? 2 : 4;      // value rows in flight together
+    typedef typename RowLoad<RowT, 1>::Raw Raw;
+    const int d = p.d;
+    f4 dn[4];
+    auto load_dense = [&](int c0) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int col = c0 + u * kColBlock + lane * 4;
+            dn[u] = (f4)(0.0f);
+            if (p.dense_in && col < d) dn[u] = load_f4_stream(p.dense_in + (size_t)v * d + col);
+        }
+    };
+    if (early) load_dense(0);
+    const int c = p.count[v];
+    if (c > p.short_max || (c == 0 && !copy)) return;
+    uint64_t addr = 0;
+    if (lane < c) addr = p.sorted[p.row_start[v] + lane].row_addr;
+    for (int c0 = 0; c0 < d; c0 += 4 * kColBlock) {
+        if (c0 > 0 || !early) load_dense(c0);
+        if (c > 0) {
+            f4 acc[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc[u] = (f4)(0.0f);
+            for (int j0 = 0; j0 < c; j0 += RB) {
+                Raw raw[RB][4];
+#pragma unroll
+                for (int t = 0; t < RB; ++t) {
+                    const uint64_t ra = bcast64(addr, min(j0 + t, c - 1));
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int col = c0 + u * kColBlock + lane * 4;
+                        raw[t][u] = Raw{};
+                        if (j0 + t < c && col < d) raw[t][u] = RowLoad<RowT, 1>::load(ra, col);
+                    }
+                }
+#pragma unroll
+                for (int t = 0; t < RB; ++t) {
+                    if (j0 + t < c) {
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            f4 r[1];
+                            RowLoad<RowT, 1>::widen(raw[t][u], r);
+                            acc[u] = acc[u] + r[0];
+                        }
+                    }
+                }
+            }
+            // dense_in has been in flight all along; the output row takes its place
+#pragma unroll
+            for (int u = 0; u < 4; ++u) dn[u] = acc[u] + dn[u];
+        }
+        // every value is there (and transformed, with an epilogue) before the first store
+        wait_vm_all();
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int col = c0 + u * kColBlock + lane * 4;
+            if (col < d) store_out<EPI>(p.dense_out, (size_t)v * d + col, dn[u], p.scale);
+        }
+    }
+}
+
+// NV: 16-byte fp32 vectors per lane (a wavefront of a piece covers 256 * NV columns); BATCH:
+// sorted positions whose rows are loaded together.
 //
-// A work-group takes kGroupPieces consecutive pieces of C sorted positions, one per wavefront,
-// and one block of columns.  A wavefront finishes the output rows of at most C pairs that start
-// in its piece; of a longer row it adds up the pairs that lie in its piece and leaves that
-// sum in LDS.  After one barrier the wavefront that holds a row's last piece within the
-// work-group adds the work-group's pieces of that row in piece order; if the row lies inside
-// the work-group it is finished there and then, otherwise the sum goes to scratch as the
-// work-group's share of the row, and the shares are combined as described above.
-template <typename RowT, int NV, int BATCH, int EPI>
+// Output rows with more than C pairs are added up by pieces.  A work-group takes kGroupPieces
+// consecutive pieces of C sorted positions, one per wavefront, and one block of columns.  A
+// wavefront adds up the pairs of such a row that lie in its piece and leaves the sum in LDS
+// (positions of shorter rows are passed over).  After one barrier the wavefront that holds a
+// row's last piece within the work-group adds the work-group's pieces of that row in piece
+// order; if the row lies inside the work-group it is finished there and then, otherwise the
+// sum goes to scratch as the work-group's share of the row, and the shares are combined as
+// described above.  The work-groups after those of the pieces take the other rows
+// (short_rows).
+template <typename RowT, int NV, int BATCH, int EPI, bool SHORT>
 __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
 {
     // [wavefront][0: of a row that began before the piece, 1: of a row that begins in it][vector][lane]
@@ -962,10 +1055,14 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
     if ((int)blockIdx.x >= p.n_piece_groups) {
-        // ---- copy: one output row per wavefront, copied if it received no pair
-        const int v = p.copy_row0 + ((int)blockIdx.x - p.n_piece_groups) * kGroupPieces + wave;
-        const uint32_t skip = (v < p.copy_row1 && p.count[v] != 0) ? 1u : 0u;
-        copy_rows<1, EPI>(p.dense_in, p.dense_out, skip, v, p.copy_row1, p.d, lane, p.scale);
+        const int v = p.row0 + ((int)blockIdx.x - p.n_piece_groups) * kGroupPieces + wave;
+        if constexpr (!SHORT) {
+            // the pieces add up every row that received pairs: copy the row if it received none
+            const uint32_t skip = (v < p.V && p.count[v] != 0) ? 1u : 0u;
+            copy_rows<1, EPI>(p.dense_in, p.dense_out, skip, v, p.V, p.d, lane, p.scale);
+        } else {
+            if (v < p.V) short_row<RowT, EPI>(p, v, lane);
+        }
         return;
     }
 
@@ -979,9 +1076,9 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
     const int pos0 = k * C;
 
     // lane j looks at sorted position pos0 + j; the window is two pieces long because
-    // an output row with at most C pairs that starts in this piece is finished here.
-    // The records are read before n_valid is known (one memory latency instead of two);
-    // what lies at or beyond n_valid is ignored.
+    // an output row with at most C pairs that starts in this piece is finished here (unless
+    // such rows are added up row by row).  The records are read before n_valid is known (one
+    // memory latency instead of two); what lies at or beyond n_valid is ignored.
     const int wpos = pos0 + lane;
     const bool inarr = lane < 2 * C && wpos < p.n;
     u4 r0 = (u4)(0u), r1 = (u4)(0u);
@@ -997,7 +1094,7 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
     const int32_t s = inwin ? (int32_t)r1.y : 0;
     const uint64_t addr = inwin ? (((uint64_t)r0.y << 32) | r0.x) : 0ull;
     const bool whole = c <= C;       // output row small enough to be summed by one wavefront
-    const bool active = inwin && (whole ? (s >= pos0 && s < pos0 + C) : (lane < C));
+    const bool active = inwin && (whole ? (!SHORT && s >= pos0 && s < pos0 + C) : (lane < C));
     const bool first = active && (wpos == s || (!whole && lane == 0));
     const bool last = active && (wpos == s + c - 1 || (!whole && lane == C - 1));
     const uint64_t A = ballot64(active);
@@ -1008,57 +1105,65 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
     const bool have_dense = p.dense_in != nullptr;
 
     if (A != 0) {
-        const int a = __builtin_ctzll(A);
-        const int b = 64 - __builtin_clzll(A);
+        typedef typename RowLoad<RowT, NV>::Raw Raw;
         f4 acc[NV];
 #pragma unroll
         for (int q = 0; q < NV; ++q) acc[q] = (f4)(0.0f);
-        for (int base = a; base < b; base += BATCH) {
-            f4 r[BATCH][NV], dn[BATCH][NV];
-#pragma unroll
-            for (int u = 0; u < BATCH; ++u) {
-                const int j = base + u;
-#pragma unroll
-                for (int q = 0; q < NV; ++q) {
-                    r[u][q] = (f4)(0.0f);
-                    dn[u][q] = (f4)(0.0f);
-                }
-                if (j < b) {
-                    const uint64_t ra = bcast64(addr, j);
-                    if (colok) RowLoad<RowT, NV>::load(ra, col, r[u]);
-                    if (have_dense && (((Lm & W) >> j) & 1ull)) {
-                        const int vj = (int)bcast((uint32_t)id, j);
-                        if (colok) {
-#pragma unroll
-                            for (int q = 0; q < NV; ++q)
-                                dn[u][q] = load_f4_stream(p.dense_in + (size_t)vj * p.d + col + 4 * q);
-                        }
-                    }
-                }
+        // The active positions are consecutive, or (when short rows are added up elsewhere) lie in
+        // two runs: the end of one long row and the beginning of another.
+        uint64_t rem = A;
+        while (rem) {
+            const int a = (int)__builtin_ctzll(rem);
+            int b = 64 - __builtin_clzll(rem);
+            if constexpr (SHORT) {
+                const uint64_t gap = ~(rem >> a);
+                b = a + (gap ? (int)__builtin_ctzll(gap) : 64 - a);
             }
+            rem &= b < 64 ? ~0ull << b : 0ull;
+            for (int base = a; base < b; base += BATCH) {
+                // all loads of a batch are issued before the first is used
+                Raw raw[BATCH];
+                f4 dn[BATCH][NV];
 #pragma unroll
-            for (int u = 0; u < BATCH; ++u) {
-                const int j = base + u;
-                if (j < b) {
-                    const bool fresh = (F >> j) & 1ull;
+                for (int u = 0; u < BATCH; ++u) {
+                    const int j = base + u;
+                    raw[u] = Raw{};
 #pragma unroll
-                    for (int q = 0; q < NV; ++q) acc[q] = (fresh ? (f4)(0.0f) : acc[q]) + r[u][q];
-                    if ((Lm >> j) & 1ull) {
-                        if ((W >> j) & 1ull) {
+                    for (int q = 0; q < NV; ++q) dn[u][q] = (f4)(0.0f);
+                    if (j < b) {
+                        if (colok) raw[u] = RowLoad<RowT, NV>::load(bcast64(addr, j), col);
+                        if (have_dense && (((Lm & W) >> j) & 1ull)) {
                             const int vj = (int)bcast((uint32_t)id, j);
                             if (colok) {
 #pragma unroll
                                 for (int q = 0; q < NV; ++q)
-                                    if constexpr (EPI == EPI_NONE)
-                                        store_f4_stream(reinterpret_cast<float*>(p.dense_out) + (size_t)vj * p.d + col + 4 * q,
-                                                        acc[q] + dn[u][q]);
-                                    else
-                                        store_out<EPI>(p.dense_out, (size_t)vj * p.d + col + 4 * q, acc[q] + dn[u][q], p.scale);
+                                    dn[u][q] = load_f4_stream(p.dense_in + (size_t)vj * p.d + col + 4 * q);
                             }
-                        } else {
-                            const int portion = (int)((H >> j) & 1ull);
+                        }
+                    }
+                }
 #pragma unroll
-                            for (int q = 0; q < NV; ++q) chain[wave][portion][q][lane] = acc[q];
+                for (int u = 0; u < BATCH; ++u) {
+                    const int j = base + u;
+                    if (j < b) {
+                        const bool fresh = (F >> j) & 1ull;
+                        f4 r[NV];
+                        RowLoad<RowT, NV>::widen(raw[u], r);
+#pragma unroll
+                        for (int q = 0; q < NV; ++q) acc[q] = (fresh ? (f4)(0.0f) : acc[q]) + r[q];
+                        if ((Lm >> j) & 1ull) {
+                            if ((W >> j) & 1ull) {
+                                const int vj = (int)bcast((uint32_t)id, j);
+                                if (colok) {
+#pragma unroll
+                                    for (int q = 0; q < NV; ++q)
+                                        store_out<EPI>(p.dense_out, (size_t)vj * p.d + col + 4 * q, acc[q] + dn[u][q], p.scale);
+                                }
+                            } else {
+                                const int portion = (int)((H >> j) & 1ull);
+#pragma unroll
+                                for (int q = 0; q < NV; ++q) chain[wave][portion][q][lane] = acc[q];
+                            }
                         }
                     }
                 }
@@ -1070,7 +1175,7 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
     // The cut rows that pass through this piece (at most two: one that ends in it or covers
     // it, one that begins in it).  The wavefront with the row's last piece inside the
     // work-group adds the work-group's pieces of the row, in piece order.
-    uint64_t cuts = Lm & ~W & A;
+    uint64_t cuts = Lm & ~W;
     const int g_first = kg * kGroupPieces, g_last = g_first + kGroupPieces - 1;
     CutRef ref[2];
 #pragma unroll
@@ -1173,6 +1278,7 @@ struct Plan {
 };
 
 int g_piece_override = 0;
+int32_t g_short_rows = -1;       // -1: choose; 0: the pieces take the short rows along; 1: row by row
 int64_t g_overlap_sort = -1;            // dense bytes (read + write) copied beside each sort launch; -1 = default
 int32_t g_part_override = 0;
 void* g_ws = nullptr;
@@ -1307,16 +1413,26 @@ void launch_timed(Kernel kernel, unsigned grid, hipStream_t stream, hipEvent_t b
         hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), 0, stream, rp);
 }
 
+template <int EPI, bool SHORT>
+void launch_reduce_as(unsigned grid, bool wide, int32_t row_dtype, hipStream_t stream, hipEvent_t begin,
+                      hipEvent_t end, const ReduceParams& rp)
+{
+    if (wide)
+        launch_timed(reduce_kernel<uint16_t, 2, 4, EPI, SHORT>, grid, stream, begin, end, rp);
+    else if (row_dtype == TS_ROW_BF16)
+        launch_timed(reduce_kernel<uint16_t, 1, 8, EPI, SHORT>, grid, stream, begin, end, rp);
+    else
+        launch_timed(reduce_kernel<float, 1, 8, EPI, SHORT>, grid, stream, begin, end, rp);
+}
+
 template <int EPI>
 void launch_reduce(unsigned grid, bool wide, int32_t row_dtype, hipStream_t stream, hipEvent_t begin,
                    hipEvent_t end, const ReduceParams& rp)
 {
-    if (wide)
-        launch_timed(reduce_kernel<uint16_t, 2, 4, EPI>, grid, stream, begin, end, rp);
-    else if (row_dtype == TS_ROW_BF16)
-        launch_timed(reduce_kernel<uint16_t, 1, 8, EPI>, grid, stream, begin, end, rp);
+    if (rp.short_max > 0)
+        launch_reduce_as<EPI, true>(grid, wide, row_dtype, stream, begin, end, rp);
     else
-        launch_timed(reduce_kernel<float, 1, 8, EPI>, grid, stream, begin, end, rp);
+        launch_reduce_as<EPI, false>(grid, wide, row_dtype, stream, begin, end, rp);
 }
 
 #define TS_DISPATCH_EPI(epi, fn, ...)                              \
@@ -1424,9 +1540,16 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     rp.logC = __builtin_ctz((unsigned)pl.C);
     rp.logG = rp.logC + kLogGroupPieces;
     rp.copy_row0 = copy_done;
-    rp.copy_row1 = tail0;
-    const int64_t copy_rows_left = skip_untouched ? 0 : tail0 - copy_done;
-    const unsigned rgrid = (unsigned)(rp.n_piece_groups + (copy_rows_left + kGroupPieces - 1) / kGroupPieces);
+    rp.copy_untouched = skip_untouched ? 0 : 1;
+    rp.row_start = sp.row_start;
+    // Output rows with at most C pairs: with many pairs in the call they are added up row by row, by the
+    // wavefronts that would otherwise copy the row; with few, the pieces take them along (measured: the calls
+    // with few pairs are mostly copying, and there the pieces' head start pays; the two meet at about 45
+    // thousand pairs for V = 32768, d = 1024).
+    rp.short_max = (g_short_rows < 0 ? n >= kShortRowsFrom : g_short_rows == 1) ? pl.C : 0;
+    // after the work-groups of the pieces, one wavefront for every output row that may need one
+    rp.row0 = rp.short_max > 0 ? 0 : (skip_untouched ? V : copy_done);
+    const unsigned rgrid = (unsigned)(rp.n_piece_groups + ((int64_t)(V - rp.row0) + kGroupPieces - 1) / kGroupPieces);
 
     const bool prof = g_prof_used < g_prof_cap && rgrid > 0;
     hipEvent_t ev_begin = prof ? g_ev[2 * g_prof_used] : nullptr;
@@ -1736,6 +1859,13 @@ int ts_set_sort_part(int32_t part)
     if (part != 0 && part != 64 && part != 128 && part != 256 && part != 512 && part != 1024 && part != kMaxPart)
         return TS_ERR_SHAPE;
     g_part_override = part;
+    return TS_OK;
+}
+
+int ts_set_short_rows(int32_t mode)
+{
+    if (mode < -1 || mode > 1) return TS_ERR_SHAPE;
+    g_short_rows = mode;
     return TS_OK;
 }
 
