@@ -23,18 +23,22 @@
 //                   The sort leaves one 32-byte record per sorted pair.
 //   reduce_kernel   the HBM-bound kernel.  First the work-groups that add value rows: each
 //                   takes four consecutive pieces of C sorted positions (one per wavefront)
-//                   and one block of 256 columns.  A wavefront finishes every output row of
-//                   at most C pairs that starts in its piece (dense_in + sum straight to
-//                   dense_out); the pieces of a longer row are added up through LDS by the
-//                   wavefront that holds the row's last piece in the work-group.  A row
-//                   that spans several work-groups leaves one fp32 share per work-group in
-//                   scratch; arrival counters tell the work-group that brings the last
-//                   share, which adds the shares in a fixed tree order, adds dense_in and
-//                   writes the row.  Then the work-groups that copy untouched output rows,
-//                   16 bytes per lane, streaming.
+//                   and one block of 256 columns.  The pieces of a row with more than C
+//                   pairs are added up through LDS by the wavefront that holds the row's
+//                   last piece in the work-group.  A row that spans several work-groups
+//                   leaves one fp32 share per work-group in scratch; arrival counters tell
+//                   the work-group that brings the last share, which adds the shares in a
+//                   fixed tree order, adds dense_in and writes the row.  Then work-groups
+//                   that take one output row per wavefront, 16 bytes per lane, streaming:
+//                   they copy the rows that received no pair.  Rows with at most C pairs:
+//                   in a call with few pairs the wavefront in whose piece such a row starts
+//                   finishes it (dense_in + sum straight to dense_out); in a call with many,
+//                   the wavefront that would copy the row adds up its few value rows
+//                   instead, and the pieces pass over them.  Same order of additions, same
+//                   bits either way.
 //
-// The sort is a chain of memory latencies that moves almost nothing, so a single-slice sort
-// launch also carries work-groups that copy dense rows [0, X) and keep HBM busy, before it
+// The sort is a chain of memory latencies that moves almost nothing, so a sort of up to six
+// slices also carries work-groups that copy dense rows [0, X) and keep HBM busy, before it
 // is known which of them receive pairs (the reduce kernel, which runs later, overwrites
 // those).  The reduce kernel copies the untouched rows of [X, V).
 //
