@@ -30,12 +30,12 @@ HBM_PEAK_GBPS = 8000.0
 # the kernel source it was taken with: when the source's hash differs, `traffic` is reported
 # as null.
 COUNTED_TRAFFIC = {
-    "source_sha256": "0db54cfb369f472330aa44904189ef9b923d2879ae8caff249d76390143748eb",
+    "source_sha256": "7308dbe0ee54acd83af65e608074dbd85c9638867454f493245de51917680abc",
     "reduce_kernel_bytes_per_launch": {
-        "transformer_big": 294.32e6,
-        "transformer_base": 112.97e6,
-        "large_batch_bf16": 573.04e6,
-        "multi_shard_stress": 1394.09e6,
+        "transformer_big": 294.34e6,
+        "transformer_base": 112.98e6,
+        "large_batch_bf16": 571.03e6,
+        "multi_shard_stress": 1385.80e6,
     },
 }
 
