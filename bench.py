@@ -30,7 +30,7 @@ HBM_PEAK_GBPS = 8000.0
 # the kernel source it was taken with: when the source's hash differs, `traffic` is reported
 # as null.
 COUNTED_TRAFFIC = {
-    "source_sha256": "7308dbe0ee54acd83af65e608074dbd85c9638867454f493245de51917680abc",
+    "source_sha256": "64b838d93e7cf115dc3fbddf9c2c486dd0f8b64a7177ab6c2b26b1a6eb970147",
     "reduce_kernel_bytes_per_launch": {
         "transformer_big": 294.34e6,
         "transformer_base": 112.98e6,

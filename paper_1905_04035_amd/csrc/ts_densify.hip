@@ -975,8 +975,8 @@ __device__ __forceinline__ void combine_if_last(const ReduceParams& p, const Cut
 template <typename RowT, int EPI>
 __device__ __forceinline__ void short_row(const ReduceParams& p, int v, int lane)
 {
-    const bool copy = p.copy_untouched && v >= p.copy_row0;
-    const bool early = copy;
+    const bool copy = p.copy_untouched && v >= p.copy_row0;    // what to do if the row received no pair
+    const bool early = copy;                                   // then only a long row makes the early load useless
     constexpr int RB = sizeof(RowT) == 4 ? 2 : 4;      // value rows in flight together
     typedef typename RowLoad<RowT, 1>::Raw Raw;
     const int d = p.d;
@@ -1028,7 +1028,7 @@ __device__ __forceinline__ void short_row(const ReduceParams& p, int v, int lane
 #pragma unroll
             for (int u = 0; u < 4; ++u) dn[u] = acc[u] + dn[u];
         }
-        // every value is there (and transformed, with an epilogue) before the first store
+        // one wait for all that is still on its way, then the stores back to back
         wait_vm_all();
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -1043,13 +1043,18 @@ __device__ __forceinline__ void short_row(const ReduceParams& p, int v, int lane
 //
 // Output rows with more than C pairs are added up by pieces.  A work-group takes kGroupPieces
 // consecutive pieces of C sorted positions, one per wavefront, and one block of columns.  A
-// wavefront adds up the pairs of such a row that lie in its piece and leaves the sum in LDS
-// (positions of shorter rows are passed over).  After one barrier the wavefront that holds a
-// row's last piece within the work-group adds the work-group's pieces of that row in piece
-// order; if the row lies inside the work-group it is finished there and then, otherwise the
-// sum goes to scratch as the work-group's share of the row, and the shares are combined as
-// described above.  The work-groups after those of the pieces take the other rows
-// (short_rows).
+// wavefront adds up the pairs of such a row that lie in its piece and leaves the sum in LDS.
+// After one barrier the wavefront that holds a row's last piece within the work-group adds
+// the work-group's pieces of that row in piece order; if the row lies inside the work-group it
+// is finished there and then, otherwise the sum goes to scratch as the work-group's share of
+// the row, and the shares are combined as described above.
+//
+// Output rows with at most C pairs, SHORT = false: the wavefront in whose piece such a row
+// starts adds it up completely (its window is two pieces long for that) and writes
+// dense_in + sum; the work-groups after those of the pieces copy the rows without pairs, one
+// per wavefront.  SHORT = true: those work-groups take every row that is not long, one per
+// wavefront (short_row), and the pieces pass over the positions of short rows.  The order of
+// additions, and so every bit of the result, is the same.
 template <typename RowT, int NV, int BATCH, int EPI, bool SHORT>
 __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
 {
