@@ -161,3 +161,24 @@ def test_the_library_chooses_by_the_number_of_pairs():
         w = wl.make_custom(V=3000, d=256, n_list=[n], zipf_s=1.2, seed=n)
         auto = run_gpu(w)["out"].view(np.uint32)
         assert np.array_equal(auto, _run_bits(w, 0)) and np.array_equal(auto, _run_bits(w, 1))
+
+
+def test_the_entry_point_with_the_built_in_workspace_row_by_row_and_over_several_slices():
+    import torch
+    w = wl.make_custom(V=8000, d=256, n_list=[60000], zipf_s=1.2, seed=98)      # four slices, short rows row by row
+    assert ts.ts_workspace_bytes(w.n_total, w.d, w.V) <= ts.TS_STATIC_SCRATCH_BYTES
+    ids_h, rows_h = w.concatenated()
+    ids, rows, dn = (torch.from_numpy(a).to("cuda:0") for a in (ids_h, rows_h, w.dense_in))
+    want = torch.empty_like(dn)
+    ws = ts.Workspace(w.n_total, w.d, w.V, "cuda:0")
+    ts.ts_densify(ids, rows, w.d, w.V, dn, want)
+    torch.cuda.synchronize()
+    assert ts.ts_last_launch_info()["sort_slices"] == 4
+    ws.close()
+    got = torch.full_like(dn, float("nan"))
+    ts.ts_densify_static(ids, rows, w.d, w.V, dn, got)
+    torch.cuda.synchronize()
+    assert torch.equal(want.view(torch.int32), got.view(torch.int32))
+    r = run_oracle(w)
+    err = np.abs(got.cpu().numpy().astype(np.float64) - r.exact)
+    assert (err <= 1e-5 * r.abs_sum).all()
