@@ -212,6 +212,10 @@ def test_tuning_setters_validate(lib):
     assert lib.ts_set_sort_part(0) == ts.TS_OK
     assert lib.ts_set_overlap_bytes(-2) == ts.TS_ERR_SHAPE
     assert lib.ts_set_overlap_bytes(-1) == ts.TS_OK
+    assert lib.ts_set_short_rows(2) == ts.TS_ERR_SHAPE
+    assert lib.ts_set_short_rows(-2) == ts.TS_ERR_SHAPE
+    assert lib.ts_set_short_rows(1) == ts.TS_OK
+    assert lib.ts_set_short_rows(-1) == ts.TS_OK
 
 
 def test_status_strings(lib):
