@@ -86,9 +86,10 @@ constexpr int kMaxSlices = 64;
 constexpr int kSliceTokens = 16384;
 constexpr int64_t kShortRowsFrom = 49152;   // calls with at least this many pairs add up their short rows row by row
 constexpr int kFusedSortMax = 57344;   // up to here one launch sorts everything (measured against two launches)
-constexpr int kPieceSmallMax = 65536;  // up to here pieces of 16 positions, above 32 (bf16 rows read 16 bytes
+constexpr int kPieceSmallMax = 96256;  // up to here pieces of 16 positions, above 32 (bf16 rows read 16 bytes
                                        // per lane: always 16) -- measured: equal up to 25600 pairs, 16 ahead by
-                                       // 1-3 % from 51200 to 80000, equal again at 100-130 thousand, 32 ahead beyond
+                                       // 1-4 % from 51200 to 131072, 32 ahead by 1 % from 200000; the limit is set
+                                       // where a call's workspace (more pieces, more shares) still fits the built-in one
 
 // ------------------------------------------------------------------ device helpers
 __device__ __forceinline__ uint64_t ballot64(bool p) { return __ballot(p); }
@@ -1038,6 +1039,176 @@ __device__ __forceinline__ void short_row(const ReduceParams& p, int v, int lane
     }
 }
 
+// Where short rows are added up row by row, the long rows are added up by wavefronts that
+// work alone: one wavefront takes a whole group of kGroupPieces pieces (4C sorted positions)
+// and one block of columns, walks the pieces one after the other and keeps in registers
+// what the work-group form keeps in LDS.  The sums are the same, in the same order: a piece's
+// pairs in sorted order, the pieces of the group in order; a row that lies inside the group is
+// finished there, of any other the group's sum becomes a share.  No barrier, no LDS, and a
+// wavefront that has to wait for its share to be acknowledged, or to combine shares, holds up
+// nobody but itself.  For groups of at most 64 sorted positions (C <= 16): one per lane.
+template <typename RowT, int NV, int EPI>
+__device__ __forceinline__ void group_wave(const ReduceParams& p, int kg, int cb, int lane)
+{
+    typedef typename RowLoad<RowT, NV>::Raw Raw;
+    constexpr int BATCH = 16;                   // value rows in flight together
+    constexpr int NW = 1;                       // windows of 64 sorted positions
+    const int C = p.C;
+    const int G = C << kLogGroupPieces;          // sorted positions of the group (at most 64)
+    const int gpos0 = kg << p.logG;
+    const int col = (cb * kColBlock + lane * 4) * NV;
+    const bool colok = col < p.d;
+    const bool have_dense = p.dense_in != nullptr;
+
+    // lane j of window w looks at sorted position gpos0 + 64 w + j; records are read before
+    // n_valid is known, what lies at or beyond it is ignored
+    u4 r0[NW], r1[NW];
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        const int jr = w * 64 + lane;
+        r0[w] = (u4)(0u);
+        r1[w] = (u4)(0u);
+        if (jr < G && gpos0 + jr < p.n) {
+            const u4* rec = reinterpret_cast<const u4*>(p.sorted + gpos0 + jr);
+            r0[w] = rec[0];
+            r1[w] = rec[1];
+        }
+    }
+    const int nvalid = *p.n_valid;
+    int32_t id[NW], c[NW], s[NW];
+    uint64_t addr[NW];
+    uint64_t L[NW], RS[NW], RE[NW];             // positions of long rows; where such a row starts; where it ends
+    bool any = false;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        const int jr = w * 64 + lane;
+        const int wpos = gpos0 + jr;
+        const bool inwin = jr < G && wpos < p.n && wpos < nvalid;
+        id[w] = inwin ? (int32_t)r0[w].z : -1;
+        c[w] = inwin ? (int32_t)r1[w].x : 0;
+        s[w] = inwin ? (int32_t)r1[w].y : 0;
+        addr[w] = inwin ? (((uint64_t)r0[w].y << 32) | r0[w].x) : 0ull;
+        const bool lng = inwin && c[w] > C;
+        L[w] = ballot64(lng);
+        RS[w] = ballot64(lng && wpos == s[w]);
+        RE[w] = ballot64(lng && wpos == s[w] + c[w] - 1);
+        any = any || L[w] != 0;
+    }
+    if (!any) return;
+    const uint64_t PS = ballot64((lane & (C - 1)) == 0);            // first and last position of a piece
+    const uint64_t PE = ballot64((lane & (C - 1)) == C - 1);        // (C divides 64)
+
+    f4 acc[NV], tot[NV];
+#pragma unroll
+    for (int q = 0; q < NV; ++q) acc[q] = tot[q] = (f4)(0.0f);
+    bool segfirst = true;       // the piece at hand is the first of its row within the group
+    CutRef ref[2];
+    ref[0].k = ref[1].k = -1;
+    int nref = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        uint64_t rem = L[w];
+        while (rem) {
+            // the next BATCH positions of long rows: all loads are issued before the first is used,
+            // dense_in of the rows that are finished among them (two at most) along with them
+            int jj[BATCH];
+            Raw raw[BATCH];
+            f4 dn[2][NV];
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int q = 0; q < NV; ++q) dn[t][q] = (f4)(0.0f);
+            int ndn = 0;
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) {
+                jj[u] = -1;
+                raw[u] = Raw{};
+                if (rem) {
+                    const int j = (int)__builtin_ctzll(rem);
+                    rem &= rem - 1ull;
+                    jj[u] = j;
+                    if (colok) raw[u] = RowLoad<RowT, NV>::load(bcast64(addr[w], j), col);
+                    if (have_dense && ((RE[w] >> j) & 1ull) && (int)bcast((uint32_t)s[w], j) >= gpos0) {
+                        const int vj = (int)bcast((uint32_t)id[w], j);
+                        if (colok) {
+#pragma unroll
+                            for (int q = 0; q < NV; ++q) {
+                                const f4 x = load_f4_stream(p.dense_in + (size_t)vj * p.d + col + 4 * q);
+                                if (ndn == 0) dn[0][q] = x; else dn[1][q] = x;
+                            }
+                        }
+                        ++ndn;
+                    }
+                }
+            }
+            int udn = 0;
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) {
+                const int j = jj[u];
+                if (j >= 0) {
+                    const bool rs = (RS[w] >> j) & 1ull, re = (RE[w] >> j) & 1ull;
+                    const bool ps = (PS >> j) & 1ull, pe = (PE >> j) & 1ull;
+                    const bool fresh = rs || ps;
+                    if (fresh) segfirst = rs || (w == 0 && j == 0);
+                    f4 r[NV];
+                    RowLoad<RowT, NV>::widen(raw[u], r);
+#pragma unroll
+                    for (int q = 0; q < NV; ++q) acc[q] = (fresh ? (f4)(0.0f) : acc[q]) + r[q];
+                    if (re || pe) {
+                        // the row's pairs in this piece are in: the pieces of the group in order
+#pragma unroll
+                        for (int q = 0; q < NV; ++q) tot[q] = segfirst ? acc[q] : tot[q] + acc[q];
+                        segfirst = false;
+                        const bool gend = w * 64 + j == G - 1;
+                        if (re || gend) {
+                            const int sj = (int)bcast((uint32_t)s[w], j);
+                            const int cj = (int)bcast((uint32_t)c[w], j);
+                            const int idj = (int)bcast((uint32_t)id[w], j);
+                            if (re && sj >= gpos0) {
+                                // the row lies inside the group
+                                f4 dj[NV];
+#pragma unroll
+                                for (int q = 0; q < NV; ++q) dj[q] = have_dense ? (udn == 0 ? dn[0][q] : dn[1][q]) : (f4)(0.0f);
+                                if (have_dense) ++udn;
+                                if (colok) {
+#pragma unroll
+                                    for (int q = 0; q < NV; ++q)
+                                        store_out<EPI>(p.dense_out, (size_t)idj * p.d + col + 4 * q, tot[q] + dj[q], p.scale);
+                                }
+                            } else {
+                                // the group's share of a row that began before it or goes on beyond it
+                                const int kg0 = (sj >> p.logC) >> kLogGroupPieces;
+                                const size_t slot = share_slot(kg0, kg - kg0);
+                                if (colok) {
+#pragma unroll
+                                    for (int q = 0; q < NV; ++q) store_f4_through(p.partial + slot * p.d + col + 4 * q, tot[q]);
+                                }
+                                CutRef x;
+                                x.k = kg;
+                                x.id = idj;
+                                x.s = sj;
+                                x.c = cj;
+                                if (nref == 0) ref[0] = x; else ref[1] = x;
+                                ++nref;
+                            }
+                        }
+                    }
+                }
+            }
+        }
+    }
+    if (nref == 0) return;
+    // shares are counted in once their stores are acknowledged; whoever brings the last share
+    // of a group of shares adds the group up
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    int answer[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) answer[t] = ref[t].k >= 0 ? announce_share(p, ref[t], cb, lane) : 0;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+        if (ref[t].k >= 0) combine_if_last<NV, EPI>(p, ref[t], cb, col, colok, lane, answer[t]);
+}
+
 // NV: 16-byte fp32 vectors per lane (a wavefront of a piece covers 256 * NV columns); BATCH:
 // sorted positions whose rows are loaded together.
 //
@@ -1055,11 +1226,13 @@ __device__ __forceinline__ void short_row(const ReduceParams& p, int v, int lane
 // per wavefront.  SHORT = true: those work-groups take every row that is not long, one per
 // wavefront (short_row), and the pieces pass over the positions of short rows.  The order of
 // additions, and so every bit of the result, is the same.
-template <typename RowT, int NV, int BATCH, int EPI, bool SHORT>
+template <typename RowT, int NV, int BATCH, int EPI, int SHORT>
 __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
 {
+    // SHORT: 0 short rows in the pieces; 1 row by row, long rows by lone wavefronts (group_wave);
+    // 2 row by row, long rows by the work-groups below
     // [wavefront][0: of a row that began before the piece, 1: of a row that begins in it][vector][lane]
-    __shared__ f4 chain[kGroupPieces][2][NV][64];
+    __shared__ f4 chain[SHORT == 1 ? 1 : kGroupPieces][2][NV][64];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -1073,6 +1246,14 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
         } else {
             if (v < p.V) short_row<RowT, EPI>(p, v, lane);
         }
+        return;
+    }
+
+    if constexpr (SHORT == 1) {
+        // four wavefronts, four consecutive groups of pieces, one block of columns
+        const int kq = (int)blockIdx.x / p.ncb;
+        const int kg = kq * 4 + wave;
+        if (kg < p.nslots / 2) group_wave<RowT, NV, EPI>(p, kg, (int)blockIdx.x - kq * p.ncb, lane);
         return;
     }
 
@@ -1423,7 +1604,7 @@ void launch_timed(Kernel kernel, unsigned grid, hipStream_t stream, hipEvent_t b
         hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), 0, stream, rp);
 }
 
-template <int EPI, bool SHORT>
+template <int EPI, int SHORT>
 void launch_reduce_as(unsigned grid, bool wide, int32_t row_dtype, hipStream_t stream, hipEvent_t begin,
                       hipEvent_t end, const ReduceParams& rp)
 {
@@ -1439,10 +1620,13 @@ template <int EPI>
 void launch_reduce(unsigned grid, bool wide, int32_t row_dtype, hipStream_t stream, hipEvent_t begin,
                    hipEvent_t end, const ReduceParams& rp)
 {
-    if (rp.short_max > 0)
-        launch_reduce_as<EPI, true>(grid, wide, row_dtype, stream, begin, end, rp);
+    // short rows row by row: long rows by lone wavefronts where a group of pieces fits the lanes of one
+    if (rp.short_max > 0 && kGroupPieces * rp.C > 64)
+        launch_reduce_as<EPI, 2>(grid, wide, row_dtype, stream, begin, end, rp);
+    else if (rp.short_max > 0)
+        launch_reduce_as<EPI, 1>(grid, wide, row_dtype, stream, begin, end, rp);
     else
-        launch_reduce_as<EPI, false>(grid, wide, row_dtype, stream, begin, end, rp);
+        launch_reduce_as<EPI, 0>(grid, wide, row_dtype, stream, begin, end, rp);
 }
 
 #define TS_DISPATCH_EPI(epi, fn, ...)                              \
@@ -1557,6 +1741,9 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     // with few pairs are mostly copying, and there the pieces' head start pays; the two meet at about 45
     // thousand pairs for V = 32768, d = 1024).
     rp.short_max = (g_short_rows < 0 ? n >= kShortRowsFrom : g_short_rows == 1) ? pl.C : 0;
+    // ... and, with pieces of at most 16 positions, their long rows by wavefronts that work alone, four groups
+    // of pieces to a work-group
+    if (rp.short_max > 0 && kGroupPieces * pl.C <= 64) rp.n_piece_groups = (pl.NBG + 3) / 4 * rp.ncb;
     // after the work-groups of the pieces, one wavefront for every output row that may need one
     rp.row0 = rp.short_max > 0 ? 0 : (skip_untouched ? V : copy_done);
     const unsigned rgrid = (unsigned)(rp.n_piece_groups + ((int64_t)(V - rp.row0) + kGroupPieces - 1) / kGroupPieces);
