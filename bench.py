@@ -30,12 +30,12 @@ HBM_PEAK_GBPS = 8000.0
 # the kernel source it was taken with: when the source's hash differs, `traffic` is reported
 # as null.
 COUNTED_TRAFFIC = {
-    "source_sha256": "64b838d93e7cf115dc3fbddf9c2c486dd0f8b64a7177ab6c2b26b1a6eb970147",
+    "source_sha256": "1bf855f9ee289faf64720b948fee72a08c79918851328377f90be421b7e53b4e",
     "reduce_kernel_bytes_per_launch": {
-        "transformer_big": 294.34e6,
-        "transformer_base": 112.98e6,
-        "large_batch_bf16": 571.03e6,
-        "multi_shard_stress": 1385.80e6,
+        "transformer_big": 294.19e6,
+        "transformer_base": 112.94e6,
+        "large_batch_bf16": 571.25e6,
+        "multi_shard_stress": 1384.79e6,
     },
 }
 

@@ -34,8 +34,10 @@
 //                   in a call with few pairs the wavefront in whose piece such a row starts
 //                   finishes it (dense_in + sum straight to dense_out); in a call with many,
 //                   the wavefront that would copy the row adds up its few value rows
-//                   instead, and the pieces pass over them.  Same order of additions, same
-//                   bits either way.
+//                   instead, and the pieces pass over them; there, with pieces of 16
+//                   positions, one wavefront walks the four pieces of a group by itself
+//                   and keeps their sums in registers (no LDS, no barrier).  Same order of
+//                   additions, same bits in every form.
 //
 // The sort is a chain of memory latencies that moves almost nothing, so a sort of up to six
 // slices also carries work-groups that copy dense rows [0, X) and keep HBM busy, before it
@@ -1220,12 +1222,14 @@ __device__ __forceinline__ void group_wave(const ReduceParams& p, int kg, int cb
 // is finished there and then, otherwise the sum goes to scratch as the work-group's share of
 // the row, and the shares are combined as described above.
 //
-// Output rows with at most C pairs, SHORT = false: the wavefront in whose piece such a row
+// Output rows with at most C pairs, SHORT = 0: the wavefront in whose piece such a row
 // starts adds it up completely (its window is two pieces long for that) and writes
 // dense_in + sum; the work-groups after those of the pieces copy the rows without pairs, one
-// per wavefront.  SHORT = true: those work-groups take every row that is not long, one per
-// wavefront (short_row), and the pieces pass over the positions of short rows.  The order of
-// additions, and so every bit of the result, is the same.
+// per wavefront.  SHORT = 1 or 2: those work-groups take every row that is not long, one per
+// wavefront (short_row), and the pieces pass over the positions of short rows; with
+// SHORT = 1 (pieces of at most 16 positions) the long rows go to wavefronts that work alone
+// (group_wave) instead of the work-groups described here.  The order of additions, and so
+// every bit of the result, is the same in all three.
 template <typename RowT, int NV, int BATCH, int EPI, int SHORT>
 __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
 {
