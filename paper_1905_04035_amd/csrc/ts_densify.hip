@@ -980,7 +980,8 @@ __device__ __forceinline__ void short_row(const ReduceParams& p, int v, int lane
 {
     const bool copy = p.copy_untouched && v >= p.copy_row0;    // what to do if the row received no pair
     const bool early = copy;                                   // then only a long row makes the early load useless
-    constexpr int RB = sizeof(RowT) == 4 ? 2 : 4;      // value rows in flight together
+    constexpr int RB = sizeof(RowT) == 4 ? 4 : 8;      // value rows in flight together (16 KiB; 8 KiB measured 2 % slower
+                                                       // where short rows have up to 32 pairs)
     typedef typename RowLoad<RowT, 1>::Raw Raw;
     const int d = p.d;
     f4 dn[4];
