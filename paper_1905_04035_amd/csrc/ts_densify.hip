@@ -86,7 +86,6 @@ constexpr int kSortWaves = 16;     // wavefronts per sort work-group
 constexpr int kColBlock = 256;     // fp32 columns per wavefront item (64 lanes x 4)
 constexpr int kMaxSlices = 64;
 constexpr int kSliceTokens = 16384;
-constexpr int64_t kShortRowsFrom = 49152;   // calls with at least this many pairs add up their short rows row by row
 constexpr int kFusedSortMax = 57344;   // up to here one launch sorts everything (measured against two launches)
 constexpr int kPieceSmallMax = 96256;  // up to here pieces of 16 positions, above 32 (bf16 rows read 16 bytes
                                        // per lane: always 16) -- measured: equal up to 25600 pairs, 16 ahead by
@@ -1493,6 +1492,22 @@ int g_prof_used = 0;
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// Calls with at least this many pairs add up their short rows row by row, the others in the pieces.
+// Row by row a wavefront has one output row's few value rows in flight, all columns of them, after
+// three loads that depend on each other; in the pieces it has up to eight pairs of 256 (bf16: 512)
+// columns in flight, and every block of columns repeats the bookkeeping.  So the wider the rows and
+// the more pairs, the better the first does.  Measured on V = 8192 .. 131072, Zipf ids: narrower than
+// 256 columns it never pays (half-empty wavefronts), at 256 from about 400 thousand pairs (2 %), at 512
+// from 65 to 100 thousand, at 1024 and more from 25 thousand (bf16 rows, 6-13 % by 50 thousand) or
+// 40-50 thousand (fp32 rows, 0.5-5 %); below those it loses up to 30 % on narrow rows and small V.
+int64_t short_rows_from(int32_t d, bool bf16)
+{
+    if (d < 256) return INT64_MAX;
+    if (d < 512) return 393216;
+    if (d < 1024) return 65536;
+    return bf16 ? 24576 : 40960;
+}
+
 int piece_tokens_for(int64_t n, bool wide_bf16)
 {
     if (g_piece_override) return g_piece_override;
@@ -1742,10 +1757,8 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     rp.copy_untouched = skip_untouched ? 0 : 1;
     rp.row_start = sp.row_start;
     // Output rows with at most C pairs: with many pairs in the call they are added up row by row, by the
-    // wavefronts that would otherwise copy the row; with few, the pieces take them along (measured: the calls
-    // with few pairs are mostly copying, and there the pieces' head start pays; the two meet at about 45
-    // thousand pairs for V = 32768, d = 1024).
-    rp.short_max = (g_short_rows < 0 ? n >= kShortRowsFrom : g_short_rows == 1) ? pl.C : 0;
+    // wavefronts that would otherwise copy the row; with few, the pieces take them along.
+    rp.short_max = (g_short_rows < 0 ? n >= short_rows_from(d, row_dtype == TS_ROW_BF16) : g_short_rows == 1) ? pl.C : 0;
     // ... and, with pieces of at most 16 positions, their long rows by wavefronts that work alone, four groups
     // of pieces to a work-group
     if (rp.short_max > 0 && kGroupPieces * pl.C <= 64) rp.n_piece_groups = (pl.NBG + 3) / 4 * rp.ncb;

@@ -156,16 +156,18 @@ def test_both_ways_give_the_same_bits_with_epilogue_and_on_normal_data():
 
 
 def test_the_library_chooses_by_the_number_of_pairs():
-    # below and above the limit the results have the bits of the forced runs
-    for n in (20000, 60000):
-        w = wl.make_custom(V=3000, d=256, n_list=[n], zipf_s=1.2, seed=n)
+    # below and above the limit (which depends on the rows' width and type) the results have the
+    # bits of the forced runs
+    for d, dt, n in [(1024, wl.ROW_FP32, 20000), (1024, wl.ROW_FP32, 60000), (1024, wl.ROW_BF16, 30000),
+                     (512, wl.ROW_FP32, 70000), (256, wl.ROW_FP32, 70000), (64, wl.ROW_BF16, 70000)]:
+        w = wl.make_custom(V=3000, d=d, n_list=[n], zipf_s=1.2, seed=n, row_dtype=dt)
         auto = run_gpu(w)["out"].view(np.uint32)
         assert np.array_equal(auto, _run_bits(w, 0)) and np.array_equal(auto, _run_bits(w, 1))
 
 
 def test_the_entry_point_with_the_built_in_workspace_row_by_row_and_over_several_slices():
     import torch
-    w = wl.make_custom(V=8000, d=256, n_list=[60000], zipf_s=1.2, seed=98)      # four slices, short rows row by row
+    w = wl.make_custom(V=8000, d=1024, n_list=[60000], zipf_s=1.2, seed=98)     # four slices, short rows row by row
     assert ts.ts_workspace_bytes(w.n_total, w.d, w.V) <= ts.TS_STATIC_SCRATCH_BYTES
     ids_h, rows_h = w.concatenated()
     ids, rows, dn = (torch.from_numpy(a).to("cuda:0") for a in (ids_h, rows_h, w.dense_in))
