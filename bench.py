@@ -30,12 +30,12 @@ HBM_PEAK_GBPS = 8000.0
 # the kernel source it was taken with: when the source's hash differs, `traffic` is reported
 # as null.
 COUNTED_TRAFFIC = {
-    "source_sha256": "734efb4dfa9e372ed06d96a4a9c1096b4fdf31336996abb9f4ec9f914994ee07",
+    "source_sha256": "d8a69efc6df8bc18a207ced2aca2ca0cfa1961dda4e44dcd50a29afa26e70fe7",
     "reduce_kernel_bytes_per_launch": {
-        "transformer_big": 294.19e6,
+        "transformer_big": 294.18e6,
         "transformer_base": 112.92e6,
-        "large_batch_bf16": 571.27e6,
-        "multi_shard_stress": 1384.81e6,
+        "large_batch_bf16": 571.24e6,
+        "multi_shard_stress": 1384.80e6,
     },
 }
 
