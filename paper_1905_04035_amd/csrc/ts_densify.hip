@@ -318,6 +318,55 @@ __device__ __forceinline__ void copy_rows(const float* dense_in, void* dense_out
     }
 }
 
+// One wavefront copies columns [c0, c0 + 1024) of dense row v (the reduce kernel's copy of a row
+// that received no pair).  A lane past the row's last column reads the row's last four columns
+// again and stores nothing: no load depends on the lane, so the four loads stay back to back.
+template <int EPI>
+__device__ __forceinline__ void copy_chunk(const float* dense_in, void* dense_out, int v, int c0, int d, int lane,
+                                           float scale)
+{
+    f4 x[4];
+    if (dense_in) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            x[u] = load_f4_stream(dense_in + (size_t)v * d + min(c0 + u * kColBlock + lane * 4, d - 4));
+    } else {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) x[u] = (f4)(0.0f);
+    }
+    // every value is transformed before the first store is issued, as in copy_rows
+    u2 packed[4];
+    if constexpr (EPI != EPI_NONE) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            x[u] = x[u] * scale;
+            if constexpr (EPI == EPI_SCALE_BF16) {
+                packed[u].x = bf16_rne(x[u].x) | (bf16_rne(x[u].y) << 16);
+                packed[u].y = bf16_rne(x[u].z) | (bf16_rne(x[u].w) << 16);
+                asm volatile("" : "+v"(packed[u]));
+            } else {
+                asm volatile("" : "+v"(x[u]));
+            }
+        }
+    }
+    // One wait for all loads: the stores sit in blocks of their own (not every lane stores), and the
+    // compiler would wait at each of them for everything before it, the store before it included.
+    // (In the copies beside the sort, copy_rows, that chain of stores is left as it is: there it
+    // measured 0.7-1 us faster per launch, the sort's own loads wait less behind gentler copies.)
+    wait_vm_all();
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int col = c0 + u * kColBlock + lane * 4;
+        if (col < d) {
+            const size_t idx = (size_t)v * d + col;
+            if constexpr (EPI == EPI_SCALE_BF16)
+                __builtin_nontemporal_store(packed[u], reinterpret_cast<u2*>(reinterpret_cast<uint16_t*>(dense_out) + idx));
+            else
+                store_f4_stream(reinterpret_cast<float*>(dense_out) + idx, x[u]);
+        }
+    }
+}
+
 // ------------------------------------------------------------------ shard table
 struct ShardTable {
     int32_t k;
@@ -822,6 +871,7 @@ struct ReduceParams {
     void* dense_out;
     float scale;
     int32_t copy_untouched;     // 0: rows without pairs are left as they are (in place, no epilogue)
+    int32_t row_chunks;         // a wavefront of those work-groups takes 1024 columns of a row: chunks per row
     // the rest
     const int32_t* row_start;
     const SortedPair* sorted;
@@ -968,14 +1018,14 @@ __device__ __forceinline__ void combine_if_last(const ReduceParams& p, const Cut
     }
 }
 
-// One output row v (all its columns), by one wavefront, when rows with at most short_max (> 0)
-// pairs are added up row by row.  A row that received no pair is copied from dense_in, unless
+// Columns [c0, c0 + 1024) of one output row v, by one wavefront, when rows with at most short_max
+// (> 0) pairs are added up row by row.  A row that received no pair is copied from dense_in, unless
 // that has been done or is not wanted; of a row that received at most short_max pairs, the
 // value rows are added up in sorted order and dense_in last.  (Longer rows belong to the
 // pieces.)  dense_in is asked for before the row's count is known whenever it will most
 // likely be needed: all but the few long rows need it then.
 template <typename RowT, int EPI>
-__device__ __forceinline__ void short_row(const ReduceParams& p, int v, int lane)
+__device__ __forceinline__ void short_row(const ReduceParams& p, int v, int c0, int lane)
 {
     const bool copy = p.copy_untouched && v >= p.copy_row0;    // what to do if the row received no pair
     const bool early = copy;                                   // then only a long row makes the early load useless
@@ -984,60 +1034,62 @@ __device__ __forceinline__ void short_row(const ReduceParams& p, int v, int lane
     typedef typename RowLoad<RowT, 1>::Raw Raw;
     const int d = p.d;
     f4 dn[4];
+    // a lane past the row's last column reads the last four columns again (and stores nothing), so
+    // that no load depends on the lane
     auto load_dense = [&](int c0) {
+        if (p.dense_in) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int col = c0 + u * kColBlock + lane * 4;
-            dn[u] = (f4)(0.0f);
-            if (p.dense_in && col < d) dn[u] = load_f4_stream(p.dense_in + (size_t)v * d + col);
+            for (int u = 0; u < 4; ++u)
+                dn[u] = load_f4_stream(p.dense_in + (size_t)v * d + min(c0 + u * kColBlock + lane * 4, d - 4));
+        } else {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) dn[u] = (f4)(0.0f);
         }
     };
-    if (early) load_dense(0);
+    if (early) load_dense(c0);
     const int c = p.count[v];
     if (c > p.short_max || (c == 0 && !copy)) return;
     uint64_t addr = 0;
     if (lane < c) addr = p.sorted[p.row_start[v] + lane].row_addr;
-    for (int c0 = 0; c0 < d; c0 += 4 * kColBlock) {
-        if (c0 > 0 || !early) load_dense(c0);
-        if (c > 0) {
-            f4 acc[4];
+    if (!early) load_dense(c0);
+    if (c > 0) {
+        f4 acc[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) acc[u] = (f4)(0.0f);
-            for (int j0 = 0; j0 < c; j0 += RB) {
-                Raw raw[RB][4];
+        for (int u = 0; u < 4; ++u) acc[u] = (f4)(0.0f);
+        for (int j0 = 0; j0 < c; j0 += RB) {
+            Raw raw[RB][4];
 #pragma unroll
-                for (int t = 0; t < RB; ++t) {
-                    const uint64_t ra = bcast64(addr, min(j0 + t, c - 1));
+            for (int t = 0; t < RB; ++t) {
+                const uint64_t ra = bcast64(addr, min(j0 + t, c - 1));
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int col = min(c0 + u * kColBlock + lane * 4, d - 4);
+                    raw[t][u] = Raw{};
+                    if (j0 + t < c) raw[t][u] = RowLoad<RowT, 1>::load(ra, col);
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < RB; ++t) {
+                if (j0 + t < c) {
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
-                        const int col = c0 + u * kColBlock + lane * 4;
-                        raw[t][u] = Raw{};
-                        if (j0 + t < c && col < d) raw[t][u] = RowLoad<RowT, 1>::load(ra, col);
-                    }
-                }
-#pragma unroll
-                for (int t = 0; t < RB; ++t) {
-                    if (j0 + t < c) {
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            f4 r[1];
-                            RowLoad<RowT, 1>::widen(raw[t][u], r);
-                            acc[u] = acc[u] + r[0];
-                        }
+                        f4 r[1];
+                        RowLoad<RowT, 1>::widen(raw[t][u], r);
+                        acc[u] = acc[u] + r[0];
                     }
                 }
             }
-            // dense_in has been in flight all along; the output row takes its place
-#pragma unroll
-            for (int u = 0; u < 4; ++u) dn[u] = acc[u] + dn[u];
         }
-        // one wait for all that is still on its way, then the stores back to back
-        wait_vm_all();
+        // dense_in has been in flight all along; the output row takes its place
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int col = c0 + u * kColBlock + lane * 4;
-            if (col < d) store_out<EPI>(p.dense_out, (size_t)v * d + col, dn[u], p.scale);
-        }
+        for (int u = 0; u < 4; ++u) dn[u] = acc[u] + dn[u];
+    }
+    // one wait for all that is still on its way, then the stores back to back
+    wait_vm_all();
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int col = c0 + u * kColBlock + lane * 4;
+        if (col < d) store_out<EPI>(p.dense_out, (size_t)v * d + col, dn[u], p.scale);
     }
 }
 
@@ -1242,13 +1294,20 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
     if ((int)blockIdx.x >= p.n_piece_groups) {
-        const int v = p.row0 + ((int)blockIdx.x - p.n_piece_groups) * kGroupPieces + wave;
+        // one wavefront per row and chunk of 1024 columns (wider rows: several wavefronts, so that
+        // no wavefront has to work through its row chunk after chunk)
+        const int item = ((int)blockIdx.x - p.n_piece_groups) * kGroupPieces + wave;
+        int v = p.row0 + item, c0 = 0;
+        if (p.row_chunks > 1) {
+            const int r = item / p.row_chunks;
+            v = p.row0 + r;
+            c0 = (item - r * p.row_chunks) * 4 * kColBlock;
+        }
         if constexpr (!SHORT) {
             // the pieces add up every row that received pairs: copy the row if it received none
-            const uint32_t skip = (v < p.V && p.count[v] != 0) ? 1u : 0u;
-            copy_rows<1, EPI>(p.dense_in, p.dense_out, skip, v, p.V, p.d, lane, p.scale);
+            if (v < p.V && p.count[v] == 0) copy_chunk<EPI>(p.dense_in, p.dense_out, v, c0, p.d, lane, p.scale);
         } else {
-            if (v < p.V) short_row<RowT, EPI>(p, v, lane);
+            if (v < p.V) short_row<RowT, EPI>(p, v, c0, lane);
         }
         return;
     }
@@ -1498,14 +1557,15 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // columns in flight, and every block of columns repeats the bookkeeping.  So the wider the rows and
 // the more pairs, the better the first does.  Measured on V = 8192 .. 131072, Zipf ids: narrower than
 // 256 columns it never pays (half-empty wavefronts), at 256 from about 400 thousand pairs (2 %), at 512
-// from 65 to 100 thousand, at 1024 and more from 25 thousand (bf16 rows, 6-13 % by 50 thousand) or
-// 40-50 thousand (fp32 rows, 0.5-5 %); below those it loses up to 30 % on narrow rows and small V.
+// from 65 to 100 thousand, at 1024 from 25 thousand (bf16 rows, 6-13 % by 50 thousand) or 40-50
+// thousand (fp32 rows, 0.5-5 %), and from there on the limit halves when the width doubles (d = 4096:
+// 8 to 16 thousand; 3-10 % beyond); below those it loses up to 30 % on narrow rows and small V.
 int64_t short_rows_from(int32_t d, bool bf16)
 {
     if (d < 256) return INT64_MAX;
     if (d < 512) return 393216;
     if (d < 1024) return 65536;
-    return bf16 ? 24576 : 40960;
+    return (int64_t)(bf16 ? 24576 : 40960) * 1024 / d;
 }
 
 int piece_tokens_for(int64_t n, bool wide_bf16)
@@ -1665,7 +1725,8 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     Plan pl;
     make_plan(n, d, V, piece_tokens_for(n, wide), &pl);
     if (!ws_v || (int64_t)pl.total > ws_bytes) return TS_ERR_WORKSPACE;
-    if ((int64_t)pl.NB * pl.ncb + V >= ((int64_t)1 << 31) - 8) return TS_ERR_OVERFLOW;
+    if ((int64_t)pl.NB * pl.ncb + (int64_t)V * ((d + 4 * kColBlock - 1) / (4 * kColBlock)) >= ((int64_t)1 << 31) - 8)
+        return TS_ERR_OVERFLOW;
     hipStream_t stream = (hipStream_t)stream_v;
     char* ws = (char*)ws_v;
 
@@ -1764,7 +1825,8 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     if (rp.short_max > 0 && kGroupPieces * pl.C <= 64) rp.n_piece_groups = (pl.NBG + 3) / 4 * rp.ncb;
     // after the work-groups of the pieces, one wavefront for every output row that may need one
     rp.row0 = rp.short_max > 0 ? 0 : (skip_untouched ? V : copy_done);
-    const unsigned rgrid = (unsigned)(rp.n_piece_groups + ((int64_t)(V - rp.row0) + kGroupPieces - 1) / kGroupPieces);
+    rp.row_chunks = (d + 4 * kColBlock - 1) / (4 * kColBlock);
+    const unsigned rgrid = (unsigned)(rp.n_piece_groups + ((int64_t)(V - rp.row0) * rp.row_chunks + kGroupPieces - 1) / kGroupPieces);
 
     const bool prof = g_prof_used < g_prof_cap && rgrid > 0;
     hipEvent_t ev_begin = prof ? g_ev[2 * g_prof_used] : nullptr;

@@ -54,7 +54,7 @@ def test_named_configurations(short_rows):
 
 
 @pytest.mark.parametrize("V,d,n", [(1, 4, 10), (7, 4, 0), (1000, 64, 2048), (1025, 260, 999), (63, 1028, 5000),
-                                   (4097, 2052, 3000)])
+                                   (4097, 2052, 3000), (301, 4100, 9000), (70, 8192, 2000)])
 def test_ragged_shapes(short_rows, V, d, n):
     w = wl.make_custom(V=V, d=d, n_list=[n // 2, n - n // 2], seed=V + d + n, integer_values=True)
     _case(w, mode="multi", exact_bits=True)

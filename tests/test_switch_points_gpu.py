@@ -19,7 +19,8 @@ def _case(V, d, n, dt, seed, **kw):
     return g
 
 
-@pytest.mark.parametrize("d,dt,limit", [(1024, wl.ROW_BF16, 24576), (1024, wl.ROW_FP32, 40960), (2052, wl.ROW_FP32, 40960),
+@pytest.mark.parametrize("d,dt,limit", [(1024, wl.ROW_BF16, 24576), (1024, wl.ROW_FP32, 40960), (2052, wl.ROW_FP32, 20440),
+                                        (4096, wl.ROW_BF16, 6144),
                                         (512, wl.ROW_FP32, 65536), (1020, wl.ROW_BF16, 65536), (256, wl.ROW_BF16, 393216),
                                         (508, wl.ROW_FP32, 393216)])
 def test_around_the_limit_between_the_two_ways_of_short_rows(d, dt, limit):
