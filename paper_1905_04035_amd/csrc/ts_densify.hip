@@ -1132,6 +1132,7 @@ __device__ __forceinline__ void group_wave(const ReduceParams& p, int kg, int cb
     int32_t id[NW], c[NW], s[NW];
     uint64_t addr[NW];
     uint64_t L[NW], RS[NW], RE[NW];             // positions of long rows; where such a row starts; where it ends
+    uint64_t INSIDE[NW];                        // positions of rows that start inside the group
     bool any = false;
 #pragma unroll
     for (int w = 0; w < NW; ++w) {
@@ -1146,6 +1147,7 @@ __device__ __forceinline__ void group_wave(const ReduceParams& p, int kg, int cb
         L[w] = ballot64(lng);
         RS[w] = ballot64(lng && wpos == s[w]);
         RE[w] = ballot64(lng && wpos == s[w] + c[w] - 1);
+        INSIDE[w] = ballot64(lng && s[w] >= gpos0);
         any = any || L[w] != 0;
     }
     if (!any) return;
@@ -1163,8 +1165,7 @@ __device__ __forceinline__ void group_wave(const ReduceParams& p, int kg, int cb
     for (int w = 0; w < NW; ++w) {
         uint64_t rem = L[w];
         while (rem) {
-            // the next BATCH positions of long rows: all loads are issued before the first is used,
-            // dense_in of the rows that are finished among them (two at most) along with them
+            // the next BATCH positions of long rows: all loads are issued before the first is used
             int jj[BATCH];
             Raw raw[BATCH];
             f4 dn[2][NV];
@@ -1172,30 +1173,38 @@ __device__ __forceinline__ void group_wave(const ReduceParams& p, int kg, int cb
             for (int t = 0; t < 2; ++t)
 #pragma unroll
                 for (int q = 0; q < NV; ++q) dn[t][q] = (f4)(0.0f);
-            int ndn = 0;
+            static_assert(BATCH == 16, "two slots, one per 8 positions");
+            // dense_in of a row that is finished here: one slot and one load instruction per half of
+            // the batch, issued behind the half's value rows.  A long row has more than 8 pairs, so
+            // no two of them end within 8 positions of long rows.  (Several conditional loads into
+            // one slot, or a slot chosen at run time, make the compiler load into a spare register
+            // and move the value afterwards, with a wait for it and for all loads before it.)
 #pragma unroll
-            for (int u = 0; u < BATCH; ++u) {
-                jj[u] = -1;
-                raw[u] = Raw{};
-                if (rem) {
-                    const int j = (int)__builtin_ctzll(rem);
-                    rem &= rem - 1ull;
-                    jj[u] = j;
-                    if (colok) raw[u] = RowLoad<RowT, NV>::load(bcast64(addr[w], j), col);
-                    if (have_dense && ((RE[w] >> j) & 1ull) && (int)bcast((uint32_t)s[w], j) >= gpos0) {
-                        const int vj = (int)bcast((uint32_t)id[w], j);
-                        if (colok) {
+            for (int h = 0; h < 2; ++h) {
+                uint64_t half = 0;
 #pragma unroll
-                            for (int q = 0; q < NV; ++q) {
-                                const f4 x = load_f4_stream(p.dense_in + (size_t)vj * p.d + col + 4 * q);
-                                if (ndn == 0) dn[0][q] = x; else dn[1][q] = x;
-                            }
-                        }
-                        ++ndn;
+                for (int uu = 0; uu < 8; ++uu) {
+                    const int u = 8 * h + uu;
+                    jj[u] = -1;
+                    raw[u] = Raw{};
+                    if (rem) {
+                        const int j = (int)__builtin_ctzll(rem);
+                        rem &= rem - 1ull;
+                        half |= 1ull << j;
+                        jj[u] = j;
+                        if (colok) raw[u] = RowLoad<RowT, NV>::load(bcast64(addr[w], j), col);
                     }
                 }
+                const uint64_t ends = half & RE[w] & INSIDE[w];
+                if (have_dense && ends && colok) {
+                    const int vj = (int)bcast((uint32_t)id[w], (int)__builtin_ctzll(ends));
+#pragma unroll
+                    for (int q = 0; q < NV; ++q) dn[h][q] = load_f4_stream(p.dense_in + (size_t)vj * p.d + col + 4 * q);
+                }
             }
-            int udn = 0;
+            // one wait for the whole batch: the compiler waits for all of it at the first use anyway, and
+            // would then wait again at every later position, which after a row's store means for that store
+            wait_vm_all();
 #pragma unroll
             for (int u = 0; u < BATCH; ++u) {
                 const int j = jj[u];
@@ -1222,8 +1231,7 @@ __device__ __forceinline__ void group_wave(const ReduceParams& p, int kg, int cb
                                 // the row lies inside the group
                                 f4 dj[NV];
 #pragma unroll
-                                for (int q = 0; q < NV; ++q) dj[q] = have_dense ? (udn == 0 ? dn[0][q] : dn[1][q]) : (f4)(0.0f);
-                                if (have_dense) ++udn;
+                                for (int q = 0; q < NV; ++q) dj[q] = have_dense ? dn[u >> 3][q] : (f4)(0.0f);
                                 if (colok) {
 #pragma unroll
                                     for (int q = 0; q < NV; ++q)
@@ -1396,6 +1404,9 @@ __global__ __launch_bounds__(256) void reduce_kernel(ReduceParams p)
                         }
                     }
                 }
+                // (where only long rows are left to the pieces, the compiler's code waits before every
+                // position for all memory operations, a finished row's store included: one wait instead)
+                if constexpr (SHORT != 0) wait_vm_all();
 #pragma unroll
                 for (int u = 0; u < BATCH; ++u) {
                     const int j = base + u;
