@@ -25,17 +25,17 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0
 
 # HBM bytes per reduce_kernel launch with default tuning, per workload, from the two
-# rocprofv3 --pmc runs summarised in profiles/ (FETCH_SIZE x 1.983 + WRITE_SIZE x 0.992, the
+# rocprofv3 --pmc runs summarised in profiles/ (FETCH_SIZE x 1.985 + WRITE_SIZE x 0.995, the
 # factors a plain copy of known size gives: profiles/counter_calibration.md).  Only valid for
 # the kernel source it was taken with: when the source's hash differs, `traffic` is reported
 # as null.
 COUNTED_TRAFFIC = {
-    "source_sha256": "d8a69efc6df8bc18a207ced2aca2ca0cfa1961dda4e44dcd50a29afa26e70fe7",
+    "source_sha256": "112c4b5818a280ff6a45d2a5457fe8129941e9ab4d527c466f38cd43ce3734a8",
     "reduce_kernel_bytes_per_launch": {
-        "transformer_big": 294.18e6,
-        "transformer_base": 112.92e6,
-        "large_batch_bf16": 571.24e6,
-        "multi_shard_stress": 1384.80e6,
+        "transformer_big": 294.80e6,
+        "transformer_base": 113.18e6,
+        "large_batch_bf16": 572.36e6,
+        "multi_shard_stress": 1387.22e6,
     },
 }
 

@@ -1657,6 +1657,21 @@ void make_plan(int64_t n, int32_t d, int32_t V, int32_t C, Plan* pl, bool bound 
 
 int check_hip(hipError_t e) { return e == hipSuccess ? TS_OK : TS_ERR_HIP; }
 
+// Compute units of the current GPU (asked once per device; 0 if the question fails, which
+// only switches a tuning rule off).
+int compute_units()
+{
+    static int cached[64] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = -1;
+        cached[dev] = n;
+    }
+    return cached[dev] > 0 ? cached[dev] : 0;
+}
+
 // Device address of the built-in workspace on the current GPU: every GPU holds its own copy
 // of the array at its own address, looked up once per device and kept.
 constexpr int kMaxDevices = 64;
@@ -1782,6 +1797,17 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
                                                : (pl.S == 1 ? budget_single : budget_multi);
     int64_t rows_per_launch = (in_place || (pl.S > 1 && epi != EPI_NONE)) ? 0 : budget / ((int64_t)8 * d);
     rows_per_launch = rows_per_launch / (kBigCopyRows * kSortWaves) * (kBigCopyRows * kSortWaves);
+    // A work-group of these launches holds a compute unit (1024 threads, most of the LDS).  Where the
+    // default budget comes to a little less than one work-group per compute unit in all, make it exactly
+    // one: fewer leave compute units idle, and a few more than one leave a second round of stragglers
+    // (measured on 256 compute units, d = 1024: 192 copying work-groups beside 64 sorting ones take
+    // 2048-12800 pairs 1-2 % faster than 136-178 do, and 208 cost 1.5 us more than 192 at 16384 pairs).
+    if (pl.S == 1 && g_overlap_sort < 0 && rows_per_launch > 0) {
+        const int64_t cus = compute_units();
+        const int64_t wg_rows = kBigCopyRows * kSortWaves;
+        const int64_t all = pl.G + rows_per_launch / wg_rows;
+        if (cus > pl.G && 4 * all >= 3 * cus && all < cus) rows_per_launch = (cus - pl.G) * wg_rows;
+    }
     const int32_t tail0 = V;
     int32_t copy_done = 0;
     auto sort_grid = [&](SortParams& q) {
