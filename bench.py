@@ -30,7 +30,7 @@ HBM_PEAK_GBPS = 8000.0
 # the kernel source it was taken with: when the source's hash differs, `traffic` is reported
 # as null.
 COUNTED_TRAFFIC = {
-    "source_sha256": "112c4b5818a280ff6a45d2a5457fe8129941e9ab4d527c466f38cd43ce3734a8",
+    "source_sha256": "69f9bb30f6c68e1b007b92e569971f078142f5677dbf200651892e6169a83294",
     "reduce_kernel_bytes_per_launch": {
         "transformer_big": 294.80e6,
         "transformer_base": 113.18e6,

@@ -1571,11 +1571,15 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // from 65 to 100 thousand, at 1024 from 25 thousand (bf16 rows, 6-13 % by 50 thousand) or 40-50
 // thousand (fp32 rows, 0.5-5 %), and from there on the limit halves when the width doubles (d = 4096:
 // 8 to 16 thousand; 3-10 % beyond); below those it loses up to 30 % on narrow rows and small V.
-int64_t short_rows_from(int32_t d, bool bf16)
+// A dense operand of half a gigabyte or more (V = 131072 at d = 1024): row by row at any number of pairs
+// (2-5 % measured from 8192 pairs on; the launch is so long that what row-by-row costs at its start and
+// end no longer counts).
+int64_t short_rows_from(int32_t d, int32_t V, bool bf16)
 {
     if (d < 256) return INT64_MAX;
     if (d < 512) return 393216;
     if (d < 1024) return 65536;
+    if ((int64_t)V * d >= ((int64_t)128 << 20)) return 0;
     return (int64_t)(bf16 ? 24576 : 40960) * 1024 / d;
 }
 
@@ -1856,7 +1860,7 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     rp.row_start = sp.row_start;
     // Output rows with at most C pairs: with many pairs in the call they are added up row by row, by the
     // wavefronts that would otherwise copy the row; with few, the pieces take them along.
-    rp.short_max = (g_short_rows < 0 ? n >= short_rows_from(d, row_dtype == TS_ROW_BF16) : g_short_rows == 1) ? pl.C : 0;
+    rp.short_max = (g_short_rows < 0 ? n >= short_rows_from(d, V, row_dtype == TS_ROW_BF16) : g_short_rows == 1) ? pl.C : 0;
     // ... and, with pieces of at most 16 positions, their long rows by wavefronts that work alone, four groups
     // of pieces to a work-group
     if (rp.short_max > 0 && kGroupPieces * pl.C <= 64) rp.n_piece_groups = (pl.NBG + 3) / 4 * rp.ncb;

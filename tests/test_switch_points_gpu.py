@@ -50,3 +50,11 @@ def test_around_whole_numbers_of_slices(k):
     for n in (4 * 16384 * k - 1, 4 * 16384 * k, 4 * 16384 * k + 1):
         g = _case(9000, 256, n, wl.ROW_FP32, seed=n, mode="multi")
         assert g["info"]["sort_slices"] == (n + 16383) // 16384
+
+
+@pytest.mark.parametrize("V,d,dt", [(131072, 1024, wl.ROW_FP32), (16384, 8192, wl.ROW_BF16)])
+def test_a_dense_operand_of_half_a_gigabyte(V, d, dt):
+    # there short rows go row by row at any number of pairs; the rows copied, all the rest checked bit for bit
+    for n in (3000, 20000):
+        g = _case(V, d, n, dt, seed=V + n, mode="multi")
+        assert g["info"]["sort_slices"] == 1
