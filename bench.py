@@ -30,12 +30,12 @@ HBM_PEAK_GBPS = 8000.0
 # the kernel source it was taken with: when the source's hash differs, `traffic` is reported
 # as null.
 COUNTED_TRAFFIC = {
-    "source_sha256": "69f9bb30f6c68e1b007b92e569971f078142f5677dbf200651892e6169a83294",
+    "source_sha256": "640438b62db24414d303824a9fb1757d02c367a95702dd997efc5107de7d3af1",
     "reduce_kernel_bytes_per_launch": {
-        "transformer_big": 294.80e6,
-        "transformer_base": 113.18e6,
-        "large_batch_bf16": 572.36e6,
-        "multi_shard_stress": 1387.22e6,
+        "transformer_big": 294.79e6,
+        "transformer_base": 113.20e6,
+        "large_batch_bf16": 568.29e6,
+        "multi_shard_stress": 1387.21e6,
     },
 }
 
