@@ -116,7 +116,8 @@ def test_scale_one_fp32_is_ts_densify_multi_bit_for_bit():
 
 
 @pytest.mark.parametrize("V,d,n_list", [(1, 4, [10]), (7, 4, [0]), (1025, 260, [999]), (333, 1028, [5000, 1]),
-                                        (5000, 264, [40000, 30000]), (64, 8, [100000])])
+                                        (5000, 264, [40000, 30000]), (64, 8, [100000]),
+                                        (300, 2052, [4000]), (150, 4100, [25000, 5000])])
 def test_ragged_shapes_both_outputs(V, d, n_list):
     w = wl.make_custom(V=V, d=d, n_list=n_list, seed=73)
     check_scaled(w, 0.3, ts.TS_OUT_FP32)
