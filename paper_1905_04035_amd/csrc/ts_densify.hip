@@ -461,24 +461,29 @@ constexpr int kListCap = 128;
 
 constexpr int kListPosBits = 21;
 
-template <bool TALLY, typename Flush>
-__device__ __forceinline__ void own_pairs(const int32_t (&idr)[kRoundTiles], int a0, int b, uint32_t pos0, int lane,
+template <bool TALLY, bool FULL, typename Flush>
+__device__ __forceinline__ void own_tiles(const int32_t (&idr)[kRoundTiles], int a0, int b, uint32_t pos0, int lane,
                                           int lo, uint32_t span, uint32_t id_base, uint32_t V_total, uint32_t* list,
                                           uint32_t cap, uint32_t& nown, uint32_t& below, uint32_t& bad,
                                           bool& flushed, Flush&& flush)
 {
+    // The tallies are kept per lane and added up over the wavefront once per round: a wavefront issues
+    // one instruction at a time whatever its kind, and 16 of them share a compute unit here, so the
+    // pass is bound by its instruction count (a ballot, a population count and a scalar add per tally
+    // and tile cost more than a compare and an add-with-carry per lane).
+    uint32_t below_l = 0, bad_l = 0;
 #pragma unroll
     for (int u = 0; u < kRoundTiles; ++u) {
-        if (a0 + u * 64 < b) {
-            const bool valid = a0 + u * 64 + lane < b;
+        if (FULL || a0 + u * 64 < b) {
+            const bool valid = FULL || a0 + u * 64 + lane < b;
             const uint32_t idg = (uint32_t)idr[u];
             const uint32_t id = idg - id_base;          // row of the call; wraps to a huge number below the range
             const uint32_t rel = id - (uint32_t)lo;
             const bool own = valid && rel < span;
             const uint64_t m = ballot64(own);
             if (TALLY) {
-                below += (uint32_t)__popcll(ballot64(valid && id < (uint32_t)lo));
-                bad += (uint32_t)__popcll(ballot64(valid && idg >= V_total));
+                below_l += (valid && id < (uint32_t)lo) ? 1u : 0u;
+                bad_l += (valid && idg >= V_total) ? 1u : 0u;
             }
             if (m) {
                 if (nown > cap - 64u) {
@@ -491,6 +496,24 @@ __device__ __forceinline__ void own_pairs(const int32_t (&idr)[kRoundTiles], int
             }
         }
     }
+    if (TALLY) {
+        below += wave_sum(below_l);
+        bad += wave_sum(bad_l);
+    }
+}
+
+// A round whose 16 tiles are all full (every round but a sub-slice's last) needs no test of the
+// lanes against the sub-slice's end.
+template <bool TALLY, typename Flush>
+__device__ __forceinline__ void own_pairs(const int32_t (&idr)[kRoundTiles], int a0, int b, uint32_t pos0, int lane,
+                                          int lo, uint32_t span, uint32_t id_base, uint32_t V_total, uint32_t* list,
+                                          uint32_t cap, uint32_t& nown, uint32_t& below, uint32_t& bad,
+                                          bool& flushed, Flush&& flush)
+{
+    if (a0 + kRoundPairs <= b)
+        own_tiles<TALLY, true>(idr, a0, b, pos0, lane, lo, span, id_base, V_total, list, cap, nown, below, bad, flushed, flush);
+    else
+        own_tiles<TALLY, false>(idr, a0, b, pos0, lane, lo, span, id_base, V_total, list, cap, nown, below, bad, flushed, flush);
 }
 
 // The counting launch of a sort that takes several slices: work-group (g, s) counts the pairs of
@@ -728,11 +751,12 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
         base_fetched = wave_sum(bl);
         nbad_fetched = wave_sum(bd);
     }
+    // every wavefront clears its own table of counts, so none has to wait for the others before it
+    // starts to list and count (the tables meet at the barrier before the scan)
     {
-        u4* const c4 = reinterpret_cast<u4*>(cnt);
-        for (int i = tid; i < kSortWaves * part / 4; i += 1024) c4[i] = (u4)(0u);
+        u4* const c4 = reinterpret_cast<u4*>(mycnt);
+        for (int i = lane; i < part / 4; i += 64) c4[i] = (u4)(0u);
     }
-    __syncthreads();
 
     // pass 1: list the owned pairs, count them per (wavefront, id); count what lies below the part
     uint32_t below = 0, bad = 0, nown = 0;
