@@ -51,6 +51,7 @@
 #include <hip/hip_ext.h>
 #include <stdint.h>
 #include <string.h>
+#include <type_traits>
 
 #include "ts_densify.h"
 #include "ts_densify_tools.h"
@@ -565,32 +566,43 @@ __global__ __launch_bounds__(1024) void count_kernel(SortParams p, ShardTable sh
     __syncthreads();
 
     uint32_t below = 0, bad = 0;
-    for (int r = 0; r < rounds; ++r) {
-        const int a0 = a + r * kRoundPairs;
-        if (r > 0) load_round(sh, j0, j1, ids0, off0, a0, b, lane, idr);
+    // (tallies per lane, full rounds without the test against the sub-slice's end: as in own_tiles)
+    uint32_t below_l = 0, bad_l = 0;
+    auto count_tiles = [&](auto full_tag, int a0) {
+        constexpr bool FULL = decltype(full_tag)::value;
 #pragma unroll
         for (int u = 0; u < kRoundTiles; ++u) {
-            if (a0 + u * 64 < b) {
-                const bool valid = a0 + u * 64 + lane < b;
+            if (FULL || a0 + u * 64 < b) {
+                const bool valid = FULL || a0 + u * 64 + lane < b;
                 const uint32_t idg = (uint32_t)idr[u];
                 const uint32_t id = idg - (uint32_t)p.id_base;      // row of the call; wraps to a huge number below the range
-                const uint32_t rel = id - (uint32_t)lo;
-                const bool own = valid && rel < span;
-                below += (uint32_t)__popcll(ballot64(valid && id < (uint32_t)lo));
-                bad += (uint32_t)__popcll(ballot64(valid && idg >= (uint32_t)p.V_total));
-                const uint64_t m = ballot64(own);
+                // a lane without a pair, or with another part's, holds no id of the part
+                const uint32_t rel = (valid && id - (uint32_t)lo < span) ? id - (uint32_t)lo : 0xFFFFFFFFu;
+                below_l += (valid && id < (uint32_t)lo) ? 1u : 0u;
+                bad_l += (valid && idg >= (uint32_t)p.V_total) ? 1u : 0u;
+                const uint64_t m = ballot64(rel != 0xFFFFFFFFu);
                 if (m) {
                     // the pairs of the id that the first owning lane holds are counted by that lane
                     // alone (a hot id would otherwise be one LDS atomic per pair), the others one by one
                     const int ll = __builtin_ctzll(m);
                     const uint32_t rl = bcast(rel, ll);
-                    const uint64_t sm = ballot64(own && rel == rl);
+                    const uint64_t sm = ballot64(rel == rl);
                     if (lane == ll) atomicAdd(&tab[rl], (uint32_t)__popcll(sm));
-                    if (own && rel != rl) atomicAdd(&tab[rel], 1u);
+                    if (rel != rl && rel != 0xFFFFFFFFu) atomicAdd(&tab[rel], 1u);
                 }
             }
         }
+    };
+    for (int r = 0; r < rounds; ++r) {
+        const int a0 = a + r * kRoundPairs;
+        if (r > 0) load_round(sh, j0, j1, ids0, off0, a0, b, lane, idr);
+        if (a0 + kRoundPairs <= b)
+            count_tiles(std::true_type{}, a0);
+        else
+            count_tiles(std::false_type{}, a0);
     }
+    below += wave_sum(below_l);
+    bad += wave_sum(bad_l);
     if (lane == 0) {
         red[w] = below;
         red[kSortWaves + w] = bad;
@@ -765,12 +777,13 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
         // the pairs of the id that the first entry holds are counted by one lane (a hot id
         // would otherwise be one LDS atomic per pair, all on one address), the others one by one
         for (uint32_t t0 = 0; t0 < cnt_l; t0 += 64) {
-            const bool has = t0 + lane < cnt_l;
-            const uint32_t rel = has ? l[t0 + lane] >> kListPosBits : 0u;
+            // a lane without an entry holds no id of the part; ballots of bare comparisons (one of a
+            // condition put together from several costs two more vector instructions)
+            const uint32_t rel = t0 + lane < cnt_l ? l[t0 + lane] >> kListPosBits : 0xFFFFFFFFu;
             const uint32_t rl = bcast(rel, 0);
-            const uint64_t sm = ballot64(has && rel == rl);
+            const uint64_t sm = ballot64(rel == rl);
             if (lane == 0) atomicAdd(&mycnt[rl], (uint32_t)__popcll(sm));
-            if (has && rel != rl) atomicAdd(&mycnt[rel], 1u);
+            if (rel != rl && rel != 0xFFFFFFFFu) atomicAdd(&mycnt[rel], 1u);
         }
     };
     for (int r = 0; r < rounds; ++r) {
@@ -822,6 +835,7 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
             const bool own = e0 + lane < cnt_l;
             const uint32_t ent = own ? l[e0 + lane] : 0u;
             const uint32_t rel = ent >> kListPosBits;
+            const uint32_t relx = own ? rel : 0xFFFFFFFFu;      // no id of the part: equal to none
             const int idx = a + (int)(ent & ((1u << kListPosBits) - 1u));
             uint64_t m = ballot64(own);
             const uint32_t basev = own ? mycnt[rel] : 0u;
@@ -832,9 +846,8 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
             while (m) {
                 const int ll = __builtin_ctzll(m);
                 const uint32_t rl = bcast(rel, ll);
-                const bool same = own && rel == rl;
-                const uint64_t sm = ballot64(same);
-                if (same) pos = basev + lanes_below(sm);
+                const uint64_t sm = ballot64(relx == rl);
+                if (relx == rl) pos = basev + lanes_below(sm);
                 if (lane == ll) {
                     leader = true;
                     next = basev + (uint32_t)__popcll(sm);
