@@ -30,7 +30,7 @@ HBM_PEAK_GBPS = 8000.0
 # the kernel source it was taken with: when the source's hash differs, `traffic` is reported
 # as null.
 COUNTED_TRAFFIC = {
-    "source_sha256": "640438b62db24414d303824a9fb1757d02c367a95702dd997efc5107de7d3af1",
+    "source_sha256": "4d221be46eabbbce249cda25ce22bf441ad0d2a0e15248c3840c517d1841312f",
     "reduce_kernel_bytes_per_launch": {
         "transformer_big": 294.79e6,
         "transformer_base": 113.20e6,
