@@ -114,21 +114,31 @@ __device__ __forceinline__ uint64_t bcast64(uint64_t x, int lane)
 // other counters left alone).  The builtin, not an asm statement: the compiler takes note of it.
 __device__ __forceinline__ void wait_vm_all() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
-__device__ __forceinline__ uint32_t wave_sum(uint32_t x)
+// Sums across the wavefront with the data-parallel-primitive moves of the vector unit (one
+// instruction and a few cycles per step; a shuffle through the LDS crossbar is an LDS instruction with
+// its latency, and six of them in a row stand in the sort work-groups' chain).  A wavefront is four
+// rows of 16 lanes.  dpp_or_zero: the value of the lane that CTRL names, 0 where there is none or
+// where the row is not in ROW_MASK.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_or_zero(uint32_t x)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, ROW_MASK, 0xf, true);
+}
+
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x, int)
+{
+    x += dpp_or_zero<0x111, 0xf>(x);        // lane - 1 of the row
+    x += dpp_or_zero<0x112, 0xf>(x);        // lane - 2
+    x += dpp_or_zero<0x114, 0xf>(x);        // lane - 4
+    x += dpp_or_zero<0x118, 0xf>(x);        // lane - 8: every row holds its own inclusive scan
+    x += dpp_or_zero<0x142, 0xa>(x);        // rows 1 and 3 add the last lane of the row before them
+    x += dpp_or_zero<0x143, 0xc>(x);        // rows 2 and 3 add lane 31, the sum of rows 0 and 1
     return x;
 }
 
-__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x, int lane)
+__device__ __forceinline__ uint32_t wave_sum(uint32_t x)
 {
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        uint32_t y = __shfl_up(x, o, 64);
-        if (lane >= o) x += y;
-    }
-    return x;
+    return __builtin_amdgcn_readlane(wave_inclusive_scan(x, 0), 63);
 }
 
 // Value rows: 4 * NV consecutive columns per lane.  load() brings them as they lie in memory
