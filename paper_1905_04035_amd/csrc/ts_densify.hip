@@ -660,9 +660,8 @@ __device__ __forceinline__ void scan_part(const SortParams& p, uint32_t* cnt, ui
     const uint32_t incl = wave_inclusive_scan(mine, lane);
     if (lane == 63) wsum[w] = incl;
     __syncthreads();
-    uint32_t woff = 0;
-    for (int ww = 0; ww < kSortWaves; ++ww)
-        if (ww < w) woff += wsum[ww];
+    // what the wavefronts before this one hold: their sums, one per lane, added up
+    const uint32_t woff = wave_sum(lane < w ? wsum[lane] : 0u);
     uint32_t rs = base + woff + incl - mine;        // first sorted position of this thread's first id
     if (idt) {
         vec start;
@@ -809,11 +808,12 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
         red[kSortWaves + w] = bad;
     }
     __syncthreads();
+    // the wavefronts' tallies, one per lane, added up across the wavefront (not 32 reads per thread)
     uint32_t below_wg = 0, bad_wg = 0;
-#pragma unroll
-    for (int ww = 0; ww < kSortWaves; ++ww) {
-        below_wg += red[ww];
-        bad_wg += red[kSortWaves + ww];
+    if (MODE == SORT_FUSED) {
+        const uint32_t t = lane < 2 * kSortWaves ? red[lane] : 0u;
+        below_wg = wave_sum(lane < kSortWaves ? t : 0u);
+        bad_wg = wave_sum(lane < kSortWaves ? 0u : t);
     }
 
     uint32_t base = below_wg, nbad = bad_wg;       // first sorted position of the part; bad ids
