@@ -30,7 +30,7 @@ HBM_PEAK_GBPS = 8000.0
 # the kernel source it was taken with: when the source's hash differs, `traffic` is reported
 # as null.
 COUNTED_TRAFFIC = {
-    "source_sha256": "4d221be46eabbbce249cda25ce22bf441ad0d2a0e15248c3840c517d1841312f",
+    "source_sha256": "424abd4f38e81429bf1c3c9108ac75bf025ce409767a3e5c18a306f00786c204",
     "reduce_kernel_bytes_per_launch": {
         "transformer_big": 294.79e6,
         "transformer_base": 113.20e6,
