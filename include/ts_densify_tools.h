@@ -75,7 +75,8 @@ int ts_set_overlap_bytes(int64_t sort_bytes);
 /*
  * Tuning.  Output rows with at most piece_tokens pairs are added up either by the pieces
  * that hold their pairs (mode 0) or row by row, by the wavefront that would otherwise copy
- * the row (mode 1).  -1 = choose from the number of pairs.  Results do not depend on it.
+ * the row (mode 1).  -1 = choose from the number of pairs, the rows' width and type and the size
+ * of the dense operand.  Results do not depend on it.
  */
 int ts_set_short_rows(int32_t mode);
 
