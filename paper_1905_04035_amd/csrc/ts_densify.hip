@@ -633,6 +633,8 @@ __global__ __launch_bounds__(1024) void count_kernel(SortParams p, ShardTable sh
 }
 
 // The scan phase of sort_kernel for one work-group (see there).  E: consecutive ids per thread.
+constexpr uint32_t kSeveral = 0x80000000u;
+
 template <int MODE, int E>
 __device__ __forceinline__ void scan_part(const SortParams& p, uint32_t* cnt, uint32_t* id_total, uint32_t* id_start,
                                           uint32_t* wsum, uint32_t base, int part, int lo, uint32_t span, int sl,
@@ -680,10 +682,15 @@ __device__ __forceinline__ void scan_part(const SortParams& p, uint32_t* cnt, ui
         }
         *reinterpret_cast<vec*>(id_total + i) = total;
         *reinterpret_cast<vec*>(id_start + i) = start;
+        // a wavefront's running position of an id, with kSeveral set if the wavefront holds the id more
+        // than once (sorted positions stay below 2^31); the ranking pass only has to work on those
         vec o = start + pre;
 #pragma unroll
         for (int ww = 0; ww < kSortWaves; ++ww) {
-            *reinterpret_cast<vec*>(cnt + ww * part + i) = o;
+            vec several;
+#pragma unroll
+            for (int e = 0; e < E; ++e) several[e] = c[ww][e] > 1u ? kSeveral : 0u;
+            *reinterpret_cast<vec*>(cnt + ww * part + i) = o | several;
             o += c[ww];
         }
     }
@@ -845,13 +852,17 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
             const bool own = e0 + lane < cnt_l;
             const uint32_t ent = own ? l[e0 + lane] : 0u;
             const uint32_t rel = ent >> kListPosBits;
-            const uint32_t relx = own ? rel : 0xFFFFFFFFu;      // no id of the part: equal to none
             const int idx = a + (int)(ent & ((1u << kListPosBits) - 1u));
-            uint64_t m = ballot64(own);
-            const uint32_t basev = own ? mycnt[rel] : 0u;
+            // An id that the wavefront holds once takes the table's position as it is.  Only ids it
+            // holds several times (flagged by the scan) go through the loop over distinct ids, which is
+            // what this pass spends its time on (13 instructions per distinct id).
+            const uint32_t tabv = own ? mycnt[rel] : 0u;
+            const uint32_t basev = tabv & ~kSeveral;
+            const uint32_t relx = tabv >= kSeveral ? rel : 0xFFFFFFFFu;     // no id to rank: equal to none
+            uint64_t m = ballot64(tabv >= kSeveral);
             const uint32_t tot_l = own ? id_total[rel] : 0u;
             const uint32_t rs_l = own ? id_start[rel] : 0u;
-            uint32_t pos = 0, next = 0;
+            uint32_t pos = basev, next = 0;
             bool leader = false;
             while (m) {
                 const int ll = __builtin_ctzll(m);
@@ -860,7 +871,7 @@ __global__ __launch_bounds__(1024) void sort_kernel(SortParams p, ShardTable sh)
                 if (relx == rl) pos = basev + lanes_below(sm);
                 if (lane == ll) {
                     leader = true;
-                    next = basev + (uint32_t)__popcll(sm);
+                    next = (basev + (uint32_t)__popcll(sm)) | kSeveral;
                 }
                 m &= ~sm;
             }
