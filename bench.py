@@ -30,7 +30,7 @@ HBM_PEAK_GBPS = 8000.0
 # the kernel source it was taken with: when the source's hash differs, `traffic` is reported
 # as null.
 COUNTED_TRAFFIC = {
-    "source_sha256": "a91c37f77b309e55eeef9ca3a1ced0d89bc1b121c9f3c3099f9d446a9b0aa7c7",
+    "source_sha256": "287ab1589c5f603a8ad060ee9744d3a5fcefaf1b23cd011b743a92346fa39cfc",
     "reduce_kernel_bytes_per_launch": {
         "transformer_big": 294.79e6,
         "transformer_base": 113.20e6,

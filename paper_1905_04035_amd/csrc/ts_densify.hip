@@ -469,6 +469,7 @@ __device__ __forceinline__ void load_round(const ShardTable& sh, int j0, int j1,
 // With TALLY the pairs with a valid id below the part and those with an id outside [0, V)
 // are counted as well (wave-uniform counts).
 constexpr int kListCap = 128;
+constexpr int kLdsBytes = 160 * 1024;       // LDS of a compute unit, the most a work-group can have
 
 constexpr int kListPosBits = 21;
 
@@ -1694,6 +1695,15 @@ void make_plan(int64_t n, int32_t d, int32_t V, int32_t C, Plan* pl, bool bound 
     // a list that holds a whole round never has to be rebuilt; parts of 2048 ids leave room
     // for short lists only
     pl->list_cap = part <= 1024 ? kRoundPairs : kListCap;
+    // One launch that walks several rounds: a wavefront whose work-group owns more of its pairs than the
+    // list holds (a dominating id) would have to walk its share a second time to rank them; give the
+    // lists what the LDS has left, up to the wavefront's whole share.
+    if (pl->S == 1 && n > (int64_t)kSortWaves * kRoundPairs && part <= 1024) {
+        const int64_t share = (pl->SL / kSortWaves + 63) / 64 * 64;
+        const int64_t room = (kLdsBytes - 256 - (int64_t)(kSortWaves + 2) * part * 4) / (kSortWaves * 4) / 64 * 64;
+        const int64_t cap = share < room ? share : room;
+        if (cap > pl->list_cap) pl->list_cap = (int32_t)cap;
+    }
     pl->G = (V + part - 1) / part;
     pl->C = C;
     pl->NB = (int32_t)((n + pl->C - 1) / pl->C);
