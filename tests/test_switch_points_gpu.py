@@ -58,3 +58,18 @@ def test_a_dense_operand_of_half_a_gigabyte(V, d, dt):
     for n in (3000, 20000):
         g = _case(V, d, n, dt, seed=V + n, mode="multi")
         assert g["info"]["sort_slices"] == 1
+
+
+@pytest.mark.parametrize("share", [0.5, 0.9])
+def test_a_dominating_id_in_a_one_launch_sort_of_several_rounds(share):
+    # half of the pairs on one id: every wavefront's list of owned pairs still holds them; nine
+    # tenths: the list overflows and the wavefront walks its share a second time
+    w = wl.make_custom(V=32768, d=64, n_list=[30000, 21200], zipf_s=1.1, seed=77, integer_values=True)
+    rng = np.random.default_rng(78)
+    for a in w.ids:
+        a[rng.random(len(a)) < share] = 12345
+    g = run_gpu(w, mode="multi")
+    assert g["info"]["sort_slices"] == 1 and g["info"]["sort_part"] == 512
+    r = run_oracle(w)
+    assert int(r.count[12345]) > share * 0.9 * w.n_total
+    check(g, r, w, exact_bits=True)
