@@ -29,17 +29,18 @@
 //                   leaves one fp32 share per work-group in scratch; arrival counters tell
 //                   the work-group that brings the last share, which adds the shares in a
 //                   fixed tree order, adds dense_in and writes the row.  Then work-groups
-//                   that take one output row per wavefront, 16 bytes per lane, streaming:
+//                   that take one output row (1024 columns of it, if it is wider) per
+//                   wavefront, 16 bytes per lane, streaming:
 //                   they copy the rows that received no pair.  Rows with at most C pairs:
-//                   in a call with few pairs the wavefront in whose piece such a row starts
-//                   finishes it (dense_in + sum straight to dense_out); in a call with many,
+//                   in a call with few pairs or narrow rows the wavefront in whose piece such
+//                   a row starts finishes it (dense_in + sum straight to dense_out); else
 //                   the wavefront that would copy the row adds up its few value rows
 //                   instead, and the pieces pass over them; there, with pieces of 16
 //                   positions, one wavefront walks the four pieces of a group by itself
 //                   and keeps their sums in registers (no LDS, no barrier).  Same order of
 //                   additions, same bits in every form.
 //
-// The sort is a chain of memory latencies that moves almost nothing, so a sort of up to six
+// The sort is a chain of latencies and instructions that moves almost nothing, so a sort of up to six
 // slices also carries work-groups that copy dense rows [0, X) and keep HBM busy, before it
 // is known which of them receive pairs (the reduce kernel, which runs later, overwrites
 // those).  The reduce kernel copies the untouched rows of [X, V).
