@@ -30,7 +30,7 @@ HBM_PEAK_GBPS = 8000.0
 # the kernel source it was taken with: when the source's hash differs, `traffic` is reported
 # as null.
 COUNTED_TRAFFIC = {
-    "source_sha256": "48e3d127576763e17735ac619547210479f153bfcb2b852574f78f3025e0563f",
+    "source_sha256": "d8a97e2228c41f6397e8d07345f6ef92847fa4099b2c55f05a629d0f02c6d588",
     "reduce_kernel_bytes_per_launch": {
         "transformer_big": 294.79e6,
         "transformer_base": 113.20e6,

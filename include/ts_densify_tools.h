@@ -43,7 +43,9 @@ int ts_call_workspace_bytes(int64_t n_total, int32_t row_dtype, int32_t d, int32
  * [0, X) were copied beside the sort launches; [2] T = V: untouched rows in [X, T) were
  * copied by the row-reduce kernel; [3] sort slices; [4] ids per sort work-group;
  * [5] pieces; [6] levels of the tree in which the shares of a cut row are added up;
- * [7] 1 if the call was in place.
+ * [7] bit 0: the call was in place; bits 1-2: how rows with at most C pairs were added up
+ * (0 in the pieces, 1 row by row with the long rows by lone wavefronts, 2 row by row with the
+ * long rows by work-groups).
  */
 int ts_last_launch_info(int32_t* info);
 

@@ -331,7 +331,10 @@ def ts_last_launch_info() -> dict:
     _check(lib().ts_last_launch_info(buf), "ts_last_launch_info")
     keys = ["piece_tokens", "sort_copy_rows_end", "reduce_copy_rows_end", "sort_slices", "sort_part",
             "pieces", "combine_levels", "in_place"]
-    return dict(zip(keys, list(buf)))
+    info = dict(zip(keys, list(buf)))
+    info["short_rows"] = info["in_place"] >> 1      # 0 in the pieces, 1 / 2 row by row
+    info["in_place"] &= 1
+    return info
 
 
 def ts_profile_begin(capacity: int) -> None:

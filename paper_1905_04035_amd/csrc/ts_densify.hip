@@ -1972,7 +1972,9 @@ int densify_impl(const ShardTable& sh, int64_t n, int32_t row_dtype, int32_t d, 
     g_last_info[4] = pl.part;
     g_last_info[5] = pl.NB;
     g_last_info[6] = pl.levels;
-    g_last_info[7] = in_place ? 1 : 0;
+    // bit 0: in place; bits 1-2: how short rows were added up (0 in the pieces, 1 row by row with the long
+    // rows by lone wavefronts, 2 row by row with the long rows by work-groups)
+    g_last_info[7] = (in_place ? 1 : 0) | ((rp.short_max == 0 ? 0 : (kGroupPieces * rp.C <= 64 ? 1 : 2)) << 1);
     g_have_last = true;
     return TS_OK;
 }

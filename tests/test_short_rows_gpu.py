@@ -158,10 +158,16 @@ def test_both_ways_give_the_same_bits_with_epilogue_and_on_normal_data():
 def test_the_library_chooses_by_the_number_of_pairs():
     # below and above the limit (which depends on the rows' width and type) the results have the
     # bits of the forced runs
-    for d, dt, n in [(1024, wl.ROW_FP32, 20000), (1024, wl.ROW_FP32, 60000), (1024, wl.ROW_BF16, 30000),
-                     (512, wl.ROW_FP32, 70000), (256, wl.ROW_FP32, 70000), (64, wl.ROW_BF16, 70000)]:
+    # (d, type, pairs, expected: 0 in the pieces, 1 row by row with lone wavefronts, 2 row by row with
+    # pieces of 32 positions in work-groups)
+    for d, dt, n, form in [(1024, wl.ROW_FP32, 20000, 0), (1024, wl.ROW_FP32, 60000, 1), (1024, wl.ROW_BF16, 30000, 1),
+                           (1024, wl.ROW_BF16, 20000, 0), (512, wl.ROW_FP32, 70000, 1), (512, wl.ROW_FP32, 60000, 0),
+                           (256, wl.ROW_FP32, 70000, 0), (64, wl.ROW_BF16, 70000, 0), (2048, wl.ROW_FP32, 21000, 1),
+                           (1024, wl.ROW_FP32, 100000, 2), (1024, wl.ROW_BF16, 100000, 1)]:
         w = wl.make_custom(V=3000, d=d, n_list=[n], zipf_s=1.2, seed=n, row_dtype=dt)
-        auto = run_gpu(w)["out"].view(np.uint32)
+        g = run_gpu(w)
+        assert g["info"]["short_rows"] == form, (d, dt, n, g["info"])
+        auto = g["out"].view(np.uint32)
         assert np.array_equal(auto, _run_bits(w, 0)) and np.array_equal(auto, _run_bits(w, 1))
 
 
